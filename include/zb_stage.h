@@ -1,0 +1,208 @@
+/*
+ * zb_stage.h — C ABI of one Zero-Bubble pipeline stage on one MI355X (gfx950).
+ *
+ * Method: "Zero Bubble Pipeline Parallelism", arXiv 2401.10241.  One pipeline
+ * stage holds L pre-LN GPT decoder layers (Sec. 2.3: FFN inner size 4h, head
+ * size h/a) and executes, per microbatch, the paper's three passes (Sec. 1):
+ *   F  forward
+ *   B  input-gradient backward   grad_x f(x,W)^T dl/dy
+ *   W  parameter-gradient backward grad_W f(x,W)^T dl/dy, accumulated over
+ *      microbatches from what B kept for it (Sec. 2.3, Table 1)
+ * in the per-stage order of the handcrafted schedules ZB-H1 (Sec. 2.1) and
+ * ZB-H2 (Sec. 2.2), followed by the post-validated optimizer step (Sec. 4)
+ * with the in-place AdamW step / rollback of Appendix C, Algorithm 1.
+ *
+ * Conventions
+ *  - Every function returns a zb_status and never throws or aborts.
+ *  - "host" pointers are ordinary CPU memory owned by the caller; "device"
+ *    pointers are HIP device memory.  The stage allocates nothing on the device:
+ *    all its device memory is carved from the caller's `arena` (device pointer,
+ *    256-byte aligned, at least zb_stage_arena_bytes() long), which must stay
+ *    valid until zb_stage_free.  Kernels run on `hip_stream` (a hipStream_t
+ *    passed as void*; NULL = the default stream).
+ *  - Calls enqueue work and return without waiting for the device, except
+ *    zb_get_tensor / zb_set_tensor / zb_synchronize / zb_profile_read and
+ *    zb_optimizer_step_validated when a report is requested.
+ *  - External tensor layout is fp32, row-major.  Token matrices are
+ *    [seq*mb_size, hidden] (sample-major rows).  Weight matrices are [in, out];
+ *    the QKV projection's columns are [Q | K | V], each head-major.
+ *  - Data type ZB_BF16: fp32 master parameters, Adam moments and accumulated
+ *    gradients; bf16 working weights, activations and activation gradients;
+ *    fp32 accumulation everywhere.  ZB_FP32: everything fp32.
+ *  - There is no CPU fallback: every pass runs in HIP kernels of this library.
+ */
+#ifndef ZB_STAGE_H
+#define ZB_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct zb_stage zb_stage; /* opaque */
+
+typedef enum {
+  ZB_OK = 0,
+  ZB_EINVAL = 1,  /* bad argument or configuration */
+  ZB_EORDER = 2,  /* F -> B -> W dependency of a microbatch violated, or pass repeated (Sec. 2) */
+  ZB_ENOMEM = 3,  /* arena too small, or a stash pool is exhausted */
+  ZB_EDEVICE = 4, /* a HIP call failed; see zb_last_error */
+  ZB_ESTATE = 5   /* call not valid in the stage's current state */
+} zb_status;
+
+typedef enum { ZB_FP32 = 0, ZB_BF16 = 1 } zb_dtype;
+typedef enum { ZB_1F1B = 0, ZB_H1 = 1, ZB_H2 = 2 } zb_kind;
+typedef enum { ZB_PASS_F = 0, ZB_PASS_B = 1, ZB_PASS_W = 2 } zb_pass;
+typedef struct { int32_t pass, mb; } zb_op;
+
+/* Per-layer parameters, in the order used by every "param index" below. */
+enum {
+  ZB_P_LN1_G = 0, ZB_P_LN1_B, ZB_P_WQKV, ZB_P_BQKV, ZB_P_WO, ZB_P_BO,
+  ZB_P_LN2_G, ZB_P_LN2_B, ZB_P_W1, ZB_P_B1, ZB_P_W2, ZB_P_B2, ZB_P_COUNT
+};
+
+/* `what` of zb_get_tensor / zb_set_tensor.  For the four per-parameter groups
+ * add the param index (ZB_T_PARAM + ZB_P_WO ...); `layer` selects the layer and
+ * `mb` is ignored.  For the per-microbatch tensors `layer` is ignored. */
+enum {
+  ZB_T_PARAM = 0,    /* fp32 master parameter                               get/set */
+  ZB_T_GRAD = 16,    /* fp32 gradient accumulated over this iteration's W   get/set */
+  ZB_T_ADAM_M = 32,  /* first moment                                        get/set */
+  ZB_T_ADAM_V = 48,  /* second moment                                       get/set */
+  ZB_T_INPUT_X = 64, /* activation received from the previous stage, [tokens, hidden]  get/set */
+  ZB_T_INPUT_DY = 65,  /* output gradient received from the next stage               get/set */
+  ZB_T_OUTPUT_Y = 66,  /* activation sent to the next stage (written by F)           get */
+  ZB_T_OUTPUT_DX = 67, /* input gradient sent to the previous stage (written by B)   get */
+  ZB_T_FLAT_PARAMS = 80, /* all master parameters of the stage, layer-major, param order, each
+                            tensor padded to a multiple of 64 floats (zb_stage_flat_count)   get */
+  ZB_T_FLAT_GRADS = 81, ZB_T_FLAT_ADAM_M = 82, ZB_T_FLAT_ADAM_V = 83
+};
+
+typedef struct {
+  int32_t layers, hidden, heads, ffn, seq, mb_size;
+  int32_t max_microbatches; /* capacity of the per-microbatch input/output buffers */
+  int32_t max_pending_b;    /* microbatches that have done F but not B at once */
+  int32_t max_pending_w;    /* microbatches that have done B but not W at once */
+  int32_t max_inflight;     /* microbatches that have done F but not W at once */
+  int32_t dtype;            /* zb_dtype */
+  int32_t journal;          /* 1: the step keeps an undo journal so that rollback restores
+                               theta, m, v bit for bit (12 B/parameter); 0: rollback is
+                               Algorithm 1's arithmetic inverse only (exact to rounding) */
+  float ln_eps;             /* 1e-5 */
+  float lr, beta1, beta2, adam_eps, weight_decay; /* Algorithm 1's gamma, beta1, beta2, eps, lambda */
+  float clip;               /* global gradient-norm clipping threshold (Sec. 4) */
+  void* hip_stream;         /* hipStream_t or NULL */
+  void* arena;              /* device memory, 256-byte aligned */
+  size_t arena_bytes;
+} zb_config;
+
+/* Fills the numeric fields of *cfg with defaults (ln_eps 1e-5, lr 1e-4, betas 0.9/0.95,
+ * eps 1e-8, weight decay 0.01, clip 1.0, journal 1, dtype bf16); shapes are left 0. */
+zb_status zb_config_defaults(zb_config* cfg);
+
+/* Device bytes zb_stage_init needs for this configuration (arena fields ignored). */
+zb_status zb_stage_arena_bytes(const zb_config* cfg, size_t* bytes);
+
+/* Creates a stage.  Parameters, moments and gradients start at zero, t = 0; load
+ * parameters with zb_set_tensor.  *out is NULL on failure. */
+zb_status zb_stage_init(const zb_config* cfg, zb_stage** out);
+zb_status zb_stage_free(zb_stage* st);
+
+/* Number of floats in the ZB_T_FLAT_* vectors. */
+zb_status zb_stage_flat_count(const zb_stage* st, size_t* count);
+
+/* Starts an iteration of m microbatches (m <= max_microbatches): forgets which passes
+ * have run, releases all stash slots and zeroes the accumulated gradients (on the stream).
+ * `iter` is recorded for error messages only.  Inputs keep their contents. */
+zb_status zb_begin_iteration(zb_stage* st, int32_t iter, int32_t m);
+
+/* The three passes of microbatch mb (Sec. 1).  F reads INPUT_X[mb] and writes OUTPUT_Y[mb];
+ * B reads INPUT_DY[mb], writes OUTPUT_DX[mb] and adds the LayerNorm gamma/beta gradients;
+ * W adds the weight and bias gradients of the four linears of every layer.
+ * ZB_EORDER unless F(mb) precedes B(mb) precedes W(mb), each at most once per iteration. */
+zb_status zb_forward(zb_stage* st, int32_t mb);
+zb_status zb_backward_input(zb_stage* st, int32_t mb);
+zb_status zb_backward_weight(zb_stage* st, int32_t mb);
+
+/* Per-stage pass order (host only; `stage` is 0-based, the paper's worker i = stage+1).
+ * Writes 3m entries to out (host, capacity cap) and their number to *n. */
+zb_status zb_schedule_order(int32_t p, int32_t stage, int32_t m, int32_t kind,
+                            zb_op* out, int32_t cap, int32_t* n);
+
+/* Largest number of pending-B, pending-W and in-flight microbatches of that order
+ * (the sizes the stash pools of zb_config need).  Any out pointer may be NULL. */
+zb_status zb_schedule_stash_need(int32_t p, int32_t stage, int32_t m, int32_t kind,
+                                 int32_t* max_pending_b, int32_t* max_pending_w, int32_t* max_inflight);
+
+/* zb_begin_iteration(m) must have been called; runs all 3m passes in schedule order. */
+zb_status zb_run_schedule(zb_stage* st, int32_t p, int32_t stage, int32_t m, int32_t kind);
+
+/* Global optimizer state contributed by the other stages (Sec. 4): the partially reduced
+ * state received from the previous stage and what the stages after this one add to it. */
+typedef struct {
+  double prev_sq, rest_sq;                 /* squared gradient norms */
+  int32_t prev_nonfinite, rest_nonfinite;  /* NaN/Inf seen there */
+  int32_t force_optimistic;                /* take the optimistic step whatever the partial state */
+} zb_global_state;
+
+enum { /* zb_step_report.outcome */
+  ZB_COMMITTED = 0,             /* optimistic step taken and confirmed by the full state */
+  ZB_SKIPPED_LOCAL = 1,         /* partial state non-finite: no step, iteration skipped */
+  ZB_ROLLED_BACK_NONFINITE = 2, /* step taken, full state non-finite: rolled back, skipped */
+  ZB_ROLLED_BACK_RECLIPPED = 3, /* step taken, full norm above threshold: rolled back, redone clipped */
+  ZB_DEFERRED_CLIPPED = 4,      /* partial norm already above threshold: one clipped step after validation */
+  ZB_DEFERRED_SKIPPED = 5       /* waited for the full state, which was non-finite: skipped */
+};
+
+typedef struct {
+  int32_t outcome;
+  int32_t stepped_optimistically;
+  double local_sq;     /* this stage's squared gradient norm */
+  double global_norm;  /* sqrt(prev_sq + local_sq + rest_sq); NaN if non-finite */
+  double clip_coef;    /* min(1, clip / (global_norm + 1e-6)); 0 if skipped */
+  int64_t t;           /* Algorithm 1's time stamp after the call */
+  uint64_t alg1_mismatch_elems; /* journal mode, on rollback: elements where Algorithm 1's
+                                   arithmetic inverse differs in any bit from the journal */
+} zb_step_report;
+
+/* Sec. 4 on the device, with no host round trip between the steps: local sum of squares and
+ * non-finite flag; partial = prev (+) local; AdamW Step predicated on the partial state;
+ * full = partial (+) rest; if the step taken was not the legitimate one, Rollback and redo
+ * Step with the full state.  All decisions are taken by the device from device-resident
+ * predicates.  report may be NULL (then the call does not wait for the device). */
+zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, zb_step_report* report);
+
+/* Copies between host fp32 buffers and stage tensors (converting to/from the stage's
+ * data type).  bytes must equal 4 * number of elements.  Both wait for the device. */
+zb_status zb_get_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, void* host_dst, size_t bytes);
+zb_status zb_set_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, const void* host_src, size_t bytes);
+
+/* Overwrites one element of INPUT_X / INPUT_DY of microbatch mb (e.g. with NaN). */
+zb_status zb_inject(zb_stage* st, int32_t what, int32_t mb, int64_t elem, float value);
+
+zb_status zb_synchronize(zb_stage* st);
+const char* zb_last_error(const zb_stage* st); /* "" if none; valid until the next call on st */
+
+/* Model FLOPs of Table 1 for this stage and m microbatches: L*m*(F + B + W) with
+ * F = sbh(24h+4s), B = sbh(24h+8s), W = 24sbh^2 (no causal discount). */
+zb_status zb_stage_model_flops(const zb_stage* st, int32_t m, double* flops);
+
+/* Per-kernel timing.  While enabled, every kernel launch is bracketed by HIP events on the
+ * stage's stream (this slows the stream down: measure throughput with profiling off).
+ * zb_profile_read waits for the device and fills up to cap rows, one per kernel class. */
+typedef struct {
+  char name[48];
+  int64_t launches;
+  double total_ms;
+  double flops;  /* algorithmic FLOPs summed over those launches (0 for bandwidth kernels) */
+  double bytes;  /* algorithmic HBM bytes summed over those launches */
+} zb_kernel_stat;
+zb_status zb_profile_enable(zb_stage* st, int32_t on); /* on=1 also clears the statistics */
+zb_status zb_profile_read(zb_stage* st, zb_kernel_stat* out, int32_t cap, int32_t* n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZB_STAGE_H */

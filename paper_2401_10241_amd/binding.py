@@ -1,0 +1,289 @@
+"""ctypes binding of libzbstage.so — argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/zb_stage.h) minus
+the ``zb_`` prefix; all arithmetic of the F / B / W passes, the schedule order and the
+optimizer protocol runs inside the library.  PyTorch is used for exactly two things:
+owning the device arena and the HIP stream.  There is no fallback: if the library is not
+built (python -m paper_2401_10241_amd.build) importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Tuple
+
+import numpy as np
+# PyTorch ships its own copy of the HIP runtime; it must be the one already in the process when
+# libzbstage.so is loaded, or the arena and the stream would belong to a different runtime.
+import torch  # noqa: F401  (device memory and streams only)
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libzbstage.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2401_10241_amd.build` "
+                      "(there is no CPU fallback)")
+lib = C.CDLL(_LIB_PATH)
+
+# ---- enums (mirroring zb_stage.h) ---------------------------------------------------------
+OK, EINVAL, EORDER, ENOMEM, EDEVICE, ESTATE = range(6)
+STATUS_NAMES = ("ZB_OK", "ZB_EINVAL", "ZB_EORDER", "ZB_ENOMEM", "ZB_EDEVICE", "ZB_ESTATE")
+FP32, BF16 = 0, 1
+KIND = {"1F1B": 0, "H1": 1, "H2": 2}
+PASS_F, PASS_B, PASS_W = 0, 1, 2
+PARAM_INDEX = {n: i for i, n in enumerate(
+    ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"))}
+T_PARAM, T_GRAD, T_ADAM_M, T_ADAM_V = 0, 16, 32, 48
+T_INPUT_X, T_INPUT_DY, T_OUTPUT_Y, T_OUTPUT_DX = 64, 65, 66, 67
+T_FLAT_PARAMS, T_FLAT_GRADS, T_FLAT_ADAM_M, T_FLAT_ADAM_V = 80, 81, 82, 83
+OUTCOME_NAMES = ("COMMITTED", "SKIPPED_LOCAL", "ROLLED_BACK_NONFINITE", "ROLLED_BACK_RECLIPPED",
+                 "DEFERRED_CLIPPED", "DEFERRED_SKIPPED")
+
+
+class zb_op(C.Structure):
+    _fields_ = [("pass_", C.c_int32), ("mb", C.c_int32)]
+
+
+class zb_config(C.Structure):
+    _fields_ = [("layers", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32), ("ffn", C.c_int32),
+                ("seq", C.c_int32), ("mb_size", C.c_int32), ("max_microbatches", C.c_int32),
+                ("max_pending_b", C.c_int32), ("max_pending_w", C.c_int32), ("max_inflight", C.c_int32),
+                ("dtype", C.c_int32), ("journal", C.c_int32), ("ln_eps", C.c_float), ("lr", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
+                ("weight_decay", C.c_float), ("clip", C.c_float), ("hip_stream", C.c_void_p),
+                ("arena", C.c_void_p), ("arena_bytes", C.c_size_t)]
+
+
+class zb_global_state(C.Structure):
+    _fields_ = [("prev_sq", C.c_double), ("rest_sq", C.c_double), ("prev_nonfinite", C.c_int32),
+                ("rest_nonfinite", C.c_int32), ("force_optimistic", C.c_int32)]
+
+
+class zb_step_report(C.Structure):
+    _fields_ = [("outcome", C.c_int32), ("stepped_optimistically", C.c_int32), ("local_sq", C.c_double),
+                ("global_norm", C.c_double), ("clip_coef", C.c_double), ("t", C.c_int64),
+                ("alg1_mismatch_elems", C.c_uint64)]
+
+
+class zb_kernel_stat(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+_P = C.POINTER
+_sig = {
+    "zb_config_defaults": [_P(zb_config)],
+    "zb_stage_arena_bytes": [_P(zb_config), _P(C.c_size_t)],
+    "zb_stage_init": [_P(zb_config), _P(C.c_void_p)],
+    "zb_stage_free": [C.c_void_p],
+    "zb_stage_flat_count": [C.c_void_p, _P(C.c_size_t)],
+    "zb_begin_iteration": [C.c_void_p, C.c_int32, C.c_int32],
+    "zb_forward": [C.c_void_p, C.c_int32],
+    "zb_backward_input": [C.c_void_p, C.c_int32],
+    "zb_backward_weight": [C.c_void_p, C.c_int32],
+    "zb_schedule_order": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P(zb_op), C.c_int32, _P(C.c_int32)],
+    "zb_schedule_stash_need": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P(C.c_int32), _P(C.c_int32),
+                               _P(C.c_int32)],
+    "zb_run_schedule": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32],
+    "zb_optimizer_step_validated": [C.c_void_p, _P(zb_global_state), _P(zb_step_report)],
+    "zb_get_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
+    "zb_set_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
+    "zb_inject": [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_float],
+    "zb_synchronize": [C.c_void_p],
+    "zb_stage_model_flops": [C.c_void_p, C.c_int32, _P(C.c_double)],
+    "zb_profile_enable": [C.c_void_p, C.c_int32],
+    "zb_profile_read": [C.c_void_p, _P(zb_kernel_stat), C.c_int32, _P(C.c_int32)],
+}
+for _name, _args in _sig.items():
+    _f = getattr(lib, _name)
+    _f.argtypes = _args
+    _f.restype = C.c_int
+lib.zb_last_error.argtypes = [C.c_void_p]
+lib.zb_last_error.restype = C.c_char_p
+EXPORTED = tuple(_sig) + ("zb_last_error",)
+
+
+class ZbError(RuntimeError):
+    def __init__(self, status: int, msg: str = ""):
+        self.status = status
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {msg}")
+
+
+def schedule_order(p: int, stage: int, m: int, kind: str) -> List[Tuple[int, int]]:
+    """zb_schedule_order: per-stage list of (pass, microbatch)."""
+    buf = (zb_op * (3 * max(m, 1)))()
+    n = C.c_int32(0)
+    rc = lib.zb_schedule_order(p, stage, m, KIND[kind], buf, 3 * max(m, 1), C.byref(n))
+    if rc != OK:
+        raise ZbError(rc, "zb_schedule_order")
+    return [(buf[i].pass_, buf[i].mb) for i in range(n.value)]
+
+
+def schedule_stash_need(p: int, stage: int, m: int, kind: str) -> Tuple[int, int, int]:
+    """zb_schedule_stash_need: (max pending-B, max pending-W, max in-flight)."""
+    a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    rc = lib.zb_schedule_stash_need(p, stage, m, KIND[kind], C.byref(a), C.byref(b), C.byref(c))
+    if rc != OK:
+        raise ZbError(rc, "zb_schedule_stash_need")
+    return a.value, b.value, c.value
+
+
+@dataclass
+class StepReport:
+    outcome: int
+    stepped_optimistically: bool
+    local_sq: float
+    global_norm: float
+    clip_coef: float
+    t: int
+    alg1_mismatch_elems: int
+
+    @property
+    def outcome_name(self) -> str:
+        return OUTCOME_NAMES[self.outcome]
+
+
+class Stage:
+    """One pipeline stage living on the current CUDA/HIP device."""
+
+    def __init__(self, *, layers, hidden, heads, ffn, seq, mb_size=1, dtype="bf16", max_microbatches,
+                 max_pending_b, max_pending_w, max_inflight, journal=True, ln_eps=1e-5, lr=1e-4, beta1=0.9,
+                 beta2=0.95, adam_eps=1e-8, weight_decay=0.01, clip=1.0, device="cuda:0", stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the zero-bubble stage runs only on the device (no CPU fallback)")
+        self._torch = torch
+        self.device = torch.device(device)
+        cfg = zb_config()
+        lib.zb_config_defaults(C.byref(cfg))
+        cfg.layers, cfg.hidden, cfg.heads, cfg.ffn, cfg.seq, cfg.mb_size = layers, hidden, heads, ffn, seq, mb_size
+        cfg.max_microbatches, cfg.max_pending_b = max_microbatches, max_pending_b
+        cfg.max_pending_w, cfg.max_inflight = max_pending_w, max_inflight
+        cfg.dtype = BF16 if dtype == "bf16" else FP32
+        cfg.journal = 1 if journal else 0
+        cfg.ln_eps, cfg.lr, cfg.beta1, cfg.beta2 = ln_eps, lr, beta1, beta2
+        cfg.adam_eps, cfg.weight_decay, cfg.clip = adam_eps, weight_decay, clip
+        need = C.c_size_t(0)
+        rc = lib.zb_stage_arena_bytes(C.byref(cfg), C.byref(need))
+        if rc != OK:
+            raise ZbError(rc, "zb_stage_arena_bytes: invalid configuration")
+        self.arena_bytes = need.value
+        with torch.cuda.device(self.device):
+            self._arena = torch.empty(need.value + 256, dtype=torch.uint8, device=self.device)
+            self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        base = (self._arena.data_ptr() + 255) // 256 * 256
+        cfg.arena, cfg.arena_bytes = base, need.value
+        cfg.hip_stream = self.stream.cuda_stream
+        self.cfg = cfg
+        self.tokens, self.hidden = seq * mb_size, hidden
+        h = C.c_void_p(None)
+        with torch.cuda.device(self.device):
+            rc = lib.zb_stage_init(C.byref(cfg), C.byref(h))
+        if rc != OK or not h.value:
+            raise ZbError(rc, "zb_stage_init")
+        self._h = h
+        n = C.c_size_t(0)
+        lib.zb_stage_flat_count(self._h, C.byref(n))
+        self.flat_count = n.value
+
+    # -- helpers ------------------------------------------------------------------------
+    def _call(self, fn, *args):
+        with self._torch.cuda.device(self.device):
+            rc = fn(self._h, *args)
+        if rc != OK:
+            raise ZbError(rc, lib.zb_last_error(self._h).decode())
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib.zb_stage_free(self._h)
+            self._h = C.c_void_p(None)
+            self._arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the C entry points ---------------------------------------------------------------
+    def begin_iteration(self, it: int, m: int):
+        self._call(lib.zb_begin_iteration, it, m)
+
+    def forward(self, mb: int):
+        self._call(lib.zb_forward, mb)
+
+    def backward_input(self, mb: int):
+        self._call(lib.zb_backward_input, mb)
+
+    def backward_weight(self, mb: int):
+        self._call(lib.zb_backward_weight, mb)
+
+    def run_schedule(self, p: int, stage: int, m: int, kind: str):
+        self._call(lib.zb_run_schedule, p, stage, m, KIND[kind])
+
+    def optimizer_step_validated(self, prev_sq=0.0, rest_sq=0.0, prev_nonfinite=False, rest_nonfinite=False,
+                                 force_optimistic=False, want_report=True) -> Optional[StepReport]:
+        gs = zb_global_state(prev_sq, rest_sq, int(prev_nonfinite), int(rest_nonfinite), int(force_optimistic))
+        if not want_report:
+            self._call(lib.zb_optimizer_step_validated, C.byref(gs), None)
+            return None
+        rep = zb_step_report()
+        self._call(lib.zb_optimizer_step_validated, C.byref(gs), C.byref(rep))
+        return StepReport(rep.outcome, bool(rep.stepped_optimistically), rep.local_sq, rep.global_norm,
+                          rep.clip_coef, rep.t, rep.alg1_mismatch_elems)
+
+    def _count(self, what: int) -> int:
+        if what < 64:
+            shp = self.param_shape(what % 16)
+            return int(np.prod(shp))
+        if what < 80:
+            return self.tokens * self.hidden
+        return self.flat_count
+
+    def param_shape(self, index: int):
+        h, f = self.cfg.hidden, self.cfg.ffn
+        return [(h,), (h,), (h, 3 * h), (3 * h,), (h, h), (h,), (h,), (h,), (h, f), (f,), (f, h), (h,)][index]
+
+    def get_tensor(self, what: int, layer: int = 0, mb: int = 0) -> np.ndarray:
+        out = np.empty(self._count(what), np.float32)
+        self._call(lib.zb_get_tensor, what, layer, mb, out.ctypes.data_as(C.c_void_p), out.nbytes)
+        if what < 64:
+            return out.reshape(self.param_shape(what % 16))
+        if what < 80:
+            return out.reshape(self.tokens, self.hidden)
+        return out
+
+    def set_tensor(self, what: int, layer: int, mb: int, value: np.ndarray):
+        v = np.ascontiguousarray(value, np.float32)
+        self._call(lib.zb_set_tensor, what, layer, mb, v.ctypes.data_as(C.c_void_p), v.nbytes)
+
+    def inject(self, what: int, mb: int, elem: int, value: float):
+        self._call(lib.zb_inject, what, mb, elem, value)
+
+    def synchronize(self):
+        self._call(lib.zb_synchronize)
+
+    def model_flops(self, m: int) -> float:
+        out = C.c_double(0)
+        self._call(lib.zb_stage_model_flops, m, C.byref(out))
+        return out.value
+
+    def profile_enable(self, on: bool):
+        self._call(lib.zb_profile_enable, int(on))
+
+    def profile_read(self):
+        buf = (zb_kernel_stat * 32)()
+        n = C.c_int32(0)
+        self._call(lib.zb_profile_read, buf, 32, C.byref(n))
+        return [dict(name=buf[i].name.decode(), launches=buf[i].launches, total_ms=buf[i].total_ms,
+                     flops=buf[i].flops, bytes=buf[i].bytes) for i in range(n.value)]
+
+    # -- convenience built only from the calls above ----------------------------------------
+    def set_params(self, params):
+        """params: list (one per layer) of dicts name -> fp32 array."""
+        for l, P in enumerate(params):
+            for name, idx in PARAM_INDEX.items():
+                self.set_tensor(T_PARAM + idx, l, 0, P[name])
+
+    def get_group(self, base: int):
+        return [{name: self.get_tensor(base + idx, l, 0) for name, idx in PARAM_INDEX.items()}
+                for l in range(self.cfg.layers)]

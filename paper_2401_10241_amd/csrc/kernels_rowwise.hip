@@ -1,0 +1,303 @@
+// Bandwidth-bound row-wise and elementwise kernels: LayerNorm forward / backward-input
+// (with the gamma/beta gradients, which this build produces in the B pass), bias-gradient
+// column sums (W pass), fills and type conversions.  One wavefront = 64 lanes; reductions
+// use cross-lane shuffles, then LDS across the four waves of a 256-thread workgroup.
+#include "zb_common.h"
+
+namespace zb {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kVec = 4;       // elements per lane per chunk
+constexpr int kMaxChunks = 8; // rows up to 256*4*8 = 8192 elements stay in registers
+
+template <typename T> struct Vec4;
+template <> struct Vec4<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct Vec4<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[4]) {
+    bf16x4 t = *reinterpret_cast<const bf16x4*>(p);
+    v[0] = (float)t[0]; v[1] = (float)t[1]; v[2] = (float)t[2]; v[3] = (float)t[3];
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[4]) {
+    bf16x4 t;
+    t[0] = (bf16_t)v[0]; t[1] = (bf16_t)v[1]; t[2] = (bf16_t)v[2]; t[3] = (bf16_t)v[3];
+    *reinterpret_cast<bf16x4*>(p) = t;
+  }
+};
+
+// sum over the 256 threads of a workgroup; every thread gets the result
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void layernorm_fwd_kernel(const T* __restrict__ x,
+                                                                 const float* __restrict__ gamma,
+                                                                 const float* __restrict__ beta,
+                                                                 T* __restrict__ out, float* __restrict__ stats,
+                                                                 int h, float eps) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const T* xr = x + row * h;
+  float v[kMaxChunks][kVec];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      Vec4<T>::load(xr + col, v[c]);
+      sum += (v[c][0] + v[c][1]) + (v[c][2] + v[c][3]);
+    }
+  }
+  const float mean = block_sum(sum, red) / (float)h;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) {
+        const float d = v[c][e] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float var = block_sum(sq, red) / (float)h;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  if (threadIdx.x == 0) {
+    stats[row * 2] = mean;
+    stats[row * 2 + 1] = rstd;
+  }
+  T* outr = out + row * h;
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      float g[4], b[4], o[4];
+      Vec4<float>::load(gamma + col, g);
+      Vec4<float>::load(beta + col, b);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) o[e] = (v[c][e] - mean) * rstd * g[e] + b[e];
+      Vec4<T>::store(outr + col, o);
+    }
+  }
+}
+
+// Each workgroup walks rows blockIdx.x, blockIdx.x + gridDim.x, ... and keeps per-column partial
+// sums of g*xhat and g in registers; they are written to partials[block][0/1][h].
+template <typename T>
+__global__ __launch_bounds__(kThreads) void layernorm_bwd_kernel(const T* __restrict__ g, const T* __restrict__ x,
+                                                                 const float* __restrict__ stats,
+                                                                 const float* __restrict__ gamma,
+                                                                 const T* __restrict__ resid, T* __restrict__ dx,
+                                                                 float* __restrict__ partials, int rows, int h) {
+  __shared__ float red[4];
+  float gam[kMaxChunks][kVec];
+  float pg[kMaxChunks][kVec], pb[kMaxChunks][kVec];
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) Vec4<float>::load(gamma + col, gam[c]);
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) pg[c][e] = pb[c][e] = 0.f;
+  }
+  for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+    const size_t off = (size_t)row * h;
+    const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+    float gg[kMaxChunks][kVec], xh[kMaxChunks][kVec];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < kMaxChunks; ++c) {
+      const int col = (c * kThreads + threadIdx.x) * kVec;
+      if (col < h) {
+        float gv[4], xv[4];
+        Vec4<T>::load(g + off + col, gv);
+        Vec4<T>::load(x + off + col, xv);
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+          xh[c][e] = (xv[e] - mean) * rstd;
+          pg[c][e] += gv[e] * xh[c][e];
+          pb[c][e] += gv[e];
+          gg[c][e] = gv[e] * gam[c][e];
+          s1 += gg[c][e];
+          s2 += gg[c][e] * xh[c][e];
+        }
+      }
+    }
+    const float m1 = block_sum(s1, red) / (float)h;
+    const float m2 = block_sum(s2, red) / (float)h;
+#pragma unroll
+    for (int c = 0; c < kMaxChunks; ++c) {
+      const int col = (c * kThreads + threadIdx.x) * kVec;
+      if (col < h) {
+        float rv[4], o[4];
+        Vec4<T>::load(resid + off + col, rv);
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) o[e] = rv[e] + rstd * (gg[c][e] - m1 - xh[c][e] * m2);
+        Vec4<T>::store(dx + off + col, o);
+      }
+    }
+  }
+  float* p0 = partials + (size_t)blockIdx.x * 2 * h;
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      Vec4<float>::store(p0 + col, pg[c]);
+      Vec4<float>::store(p0 + h + col, pb[c]);
+    }
+  }
+}
+
+// dgamma[c] += sum_b partials[b][0][c]; dbeta[c] += sum_b partials[b][1][c]   (fixed order)
+__global__ void layernorm_bwd_reduce_kernel(const float* __restrict__ partials, float* __restrict__ dgamma,
+                                            float* __restrict__ dbeta, int blocks, int h) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= h) return;
+  float a = 0.f, b = 0.f;
+  for (int k = 0; k < blocks; ++k) {
+    a += partials[(size_t)k * 2 * h + col];
+    b += partials[(size_t)k * 2 * h + h + col];
+  }
+  dgamma[col] += a;
+  dbeta[col] += b;
+}
+
+// 256 threads = 16 column-lanes (each kV consecutive columns) x 16 row groups
+template <typename T, int kV>
+__global__ __launch_bounds__(kThreads) void colsum_accum_kernel(const T* __restrict__ dy, float* __restrict__ db,
+                                                                int rows, int n) {
+  __shared__ float red[16][16 * kV + 1];
+  const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
+  const int col = (blockIdx.x * 16 + cl) * kV;
+  float acc[kV];
+#pragma unroll
+  for (int e = 0; e < kV; ++e) acc[e] = 0.f;
+  if (col < n) {
+    for (int r = rg; r < rows; r += 16) {
+      const T* p = dy + (size_t)r * n + col;
+#pragma unroll
+      for (int e = 0; e < kV; e += 4) {
+        float v[4];
+        Vec4<T>::load(p + e, v);
+        acc[e] += v[0]; acc[e + 1] += v[1]; acc[e + 2] += v[2]; acc[e + 3] += v[3];
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < kV; ++e) red[rg][cl * kV + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < 16 * kV) {
+    const int c = blockIdx.x * 16 * kV + threadIdx.x;
+    if (c < n) {
+      float t = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t += red[r][threadIdx.x];
+      db[c] += t;
+    }
+  }
+}
+
+__global__ void fill_f32_kernel(float* p, size_t n, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+template <typename T>
+__global__ void convert_from_f32_kernel(const float* __restrict__ s, T* __restrict__ d, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) d[i] = from_f32<T>(s[i]);
+}
+template <typename T>
+__global__ void convert_to_f32_kernel(const T* __restrict__ s, float* __restrict__ d, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) d[i] = to_f32(s[i]);
+}
+template <typename T> __global__ void poke_kernel(T* d, size_t idx, float v) { d[idx] = from_f32<T>(v); }
+
+inline int grid_for(size_t n) {
+  size_t b = (n + 255) / 256;
+  return (int)(b < 1 ? 1 : (b > 4096 ? 4096 : b));
+}
+
+}  // namespace
+
+template <typename T>
+hipError_t launch_layernorm_fwd(const T* x, const float* gamma, const float* beta, T* out, float* stats, int rows,
+                                int h, float eps, hipStream_t s) {
+  if (h % kVec != 0 || h > kThreads * kVec * kMaxChunks || rows <= 0) return hipErrorInvalidValue;
+  layernorm_fwd_kernel<T><<<rows, kThreads, 0, s>>>(x, gamma, beta, out, stats, h, eps);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid,
+                                T* dx, float* dgamma, float* dbeta, float* partials, int rows, int h,
+                                hipStream_t s) {
+  if (h % kVec != 0 || h > kThreads * kVec * kMaxChunks || rows <= 0) return hipErrorInvalidValue;
+  const int blocks = rows < kLnBwdBlocks ? rows : kLnBwdBlocks;
+  layernorm_bwd_kernel<T><<<blocks, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, partials, rows, h);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  layernorm_bwd_reduce_kernel<<<(h + 255) / 256, 256, 0, s>>>(partials, dgamma, dbeta, blocks, h);
+  return hipGetLastError();
+}
+
+template <typename T> hipError_t launch_colsum_accum(const T* dy, float* db, int rows, int n, hipStream_t s) {
+  constexpr int kV = 16 / sizeof(T);
+  if (n % kV != 0 || rows <= 0) return hipErrorInvalidValue;
+  const int per_block = 16 * kV;
+  colsum_accum_kernel<T, kV><<<(n + per_block - 1) / per_block, kThreads, 0, s>>>(dy, db, rows, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  fill_f32_kernel<<<grid_for(n), 256, 0, s>>>(p, n, v);
+  return hipGetLastError();
+}
+template <typename T> hipError_t launch_convert_from_f32(const float* src, T* dst, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  convert_from_f32_kernel<T><<<grid_for(n), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+template <typename T> hipError_t launch_convert_to_f32(const T* src, float* dst, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  convert_to_f32_kernel<T><<<grid_for(n), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStream_t s) {
+  poke_kernel<T><<<1, 1, 0, s>>>(dst, idx, v);
+  return hipGetLastError();
+}
+
+#define ZB_INST(T)                                                                                              \
+  template hipError_t launch_layernorm_fwd<T>(const T*, const float*, const float*, T*, float*, int, int, float, \
+                                              hipStream_t);                                                      \
+  template hipError_t launch_layernorm_bwd<T>(const T*, const T*, const float*, const float*, const T*, T*,      \
+                                              float*, float*, float*, int, int, hipStream_t);                    \
+  template hipError_t launch_colsum_accum<T>(const T*, float*, int, int, hipStream_t);                           \
+  template hipError_t launch_convert_from_f32<T>(const float*, T*, size_t, hipStream_t);                         \
+  template hipError_t launch_convert_to_f32<T>(const T*, float*, size_t, hipStream_t);                           \
+  template hipError_t launch_poke<T>(T*, size_t, float, hipStream_t);
+ZB_INST(float)
+ZB_INST(bf16_t)
+#undef ZB_INST
+
+}  // namespace zb

@@ -1,0 +1,836 @@
+// Host side of the zero-bubble stage library: the C ABI of include/zb_stage.h, the per-stage pass
+// order of 1F1B / ZB-H1 / ZB-H2, the stash pools with the F -> B -> W life cycle, the pass
+// executors and the post-validated optimizer protocol.  All arithmetic runs in the HIP kernels
+// declared in zb_common.h; nothing here computes on the CPU.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/zb_stage.h"
+#include "zb_common.h"
+
+using namespace zb;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+
+struct Bump {  // carves the arena; with base == nullptr it only measures
+  char* base;
+  size_t off = 0;
+  explicit Bump(void* b) : base((char*)b) {}
+  template <typename T> T* take(size_t bytes) {
+    off = align_up(off);
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+struct LayerOff {  // byte offsets inside one slot of each pool
+  size_t fb_x, fb_qkv, fb_y1, fb_fh, fb_stats1, fb_stats2, fb_lse;
+  size_t fw_a, fw_c, fw_u, fw_g;
+  size_t bw_dqkv, bw_dy1, bw_dfh, bw_dy;
+};
+
+enum KClass {
+  KC_GEMM_FWD = 0, KC_GEMM_DGRAD, KC_GEMM_WGRAD, KC_ATTN_FWD, KC_ATTN_BWD, KC_LN_FWD, KC_LN_BWD, KC_COLSUM,
+  KC_FILL, KC_SUMSQ, KC_ADAMW_STEP, KC_ADAMW_ROLLBACK, KC_COUNT
+};
+const char* const kClassNames[KC_COUNT] = {
+    "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd", "layernorm_bwd",
+    "bias_grad_colsum", "grad_zero_fill", "grad_sumsq", "adamw_step", "adamw_rollback"};
+
+struct ProfRec {
+  int cls;
+  hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct zb_stage {
+  zb_config cfg;
+  hipStream_t stream = nullptr;
+  bool bf16 = true;
+  int L = 0, h = 0, a = 0, ffn = 0, s = 0, b = 0, T = 0, d = 0;
+  size_t esz = 2;
+
+  // flat fp32 vectors: [layer][param], each tensor padded to 64 floats
+  size_t flat_count = 0;
+  std::vector<size_t> poff;  // L * ZB_P_COUNT
+  size_t pcount[ZB_P_COUNT];
+  float *theta = nullptr, *grad = nullptr, *adam_m = nullptr, *adam_v = nullptr;
+  float *j_theta = nullptr, *j_m = nullptr, *j_v = nullptr;
+  bf16_t* theta16 = nullptr;
+
+  char *in_x = nullptr, *in_dy = nullptr, *out_y = nullptr, *out_dx = nullptr;
+  size_t act_bytes = 0;  // one [T, h] tensor
+
+  char *fb_pool = nullptr, *fw_pool = nullptr, *bw_pool = nullptr;
+  size_t fb_slot = 0, fw_slot = 0, bw_slot = 0;
+  std::vector<LayerOff> lo;
+  std::vector<int> free_fb, free_fw, free_bw, slot_fb, slot_fw, slot_bw;
+  std::vector<unsigned char> done[3];
+  int m = 0, iter = 0;
+
+  char* tmp = nullptr;  // [T, h] activation-gradient scratch
+  float *dvec = nullptr, *ln_partials = nullptr, *staging = nullptr;
+  size_t staging_floats = 0;
+  double* partial_sq = nullptr;
+  int* partial_nf = nullptr;
+  OptDevState* opt = nullptr;
+  OptHyper hp;
+
+  std::string err;
+  bool profiling = false;
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> ev_pool;
+  double prof_flops[KC_COUNT], prof_bytes[KC_COUNT];
+
+  float* P(int l, int i) const { return theta + poff[l * ZB_P_COUNT + i]; }
+  float* G(int l, int i) const { return grad + poff[l * ZB_P_COUNT + i]; }
+  const void* Wt(int l, int i) const {
+    return bf16 ? (const void*)(theta16 + poff[l * ZB_P_COUNT + i]) : (const void*)P(l, i);
+  }
+};
+
+namespace {
+
+zb_status fail(zb_stage* st, zb_status code, const std::string& msg) {
+  if (st) st->err = msg;
+  return code;
+}
+#define ZB_HIP(st, expr)                                                                             \
+  do {                                                                                               \
+    hipError_t e__ = (expr);                                                                         \
+    if (e__ != hipSuccess)                                                                           \
+      return fail(st, ZB_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e__));               \
+  } while (0)
+
+struct ProfScope {  // brackets one kernel launch with events when profiling is on
+  zb_stage* st;
+  hipEvent_t b = nullptr;
+  bool on;
+  ProfScope(zb_stage* s, int cls, double flops, double bytes) : st(s), on(s->profiling) {
+    if (!on) return;
+    hipEvent_t a = take();
+    b = take();
+    if (!a || !b) { on = false; return; }
+    st->prof.push_back({cls, a, b});
+    st->prof_flops[cls] += flops;
+    st->prof_bytes[cls] += bytes;
+    (void)hipEventRecord(a, st->stream);
+  }
+  ~ProfScope() {
+    if (on) (void)hipEventRecord(b, st->stream);
+  }
+  hipEvent_t take() {
+    if (!st->ev_pool.empty()) {
+      hipEvent_t e = st->ev_pool.back();
+      st->ev_pool.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+
+bool valid_shapes(const zb_config* c, std::string* why) {
+  auto bad = [&](const char* m) { *why = m; return false; };
+  if (!c) return bad("null config");
+  if (c->layers < 1 || c->hidden < 1 || c->heads < 1 || c->ffn < 1 || c->seq < 1 || c->mb_size < 1)
+    return bad("layers, hidden, heads, ffn, seq, mb_size must be positive");
+  if (c->hidden % c->heads != 0) return bad("hidden must be a multiple of heads");
+  if (c->hidden % 8 != 0 || c->ffn % 8 != 0) return bad("hidden and ffn must be multiples of 8");
+  if (c->hidden > 8192) return bad("hidden above 8192 is not supported by the LayerNorm kernels");
+  if (c->max_microbatches < 1 || c->max_pending_b < 1 || c->max_pending_w < 1 || c->max_inflight < 1)
+    return bad("max_microbatches, max_pending_b, max_pending_w, max_inflight must be positive");
+  if (c->dtype != ZB_FP32 && c->dtype != ZB_BF16) return bad("dtype must be ZB_FP32 or ZB_BF16");
+  if ((long long)c->seq * c->mb_size > (1 << 24)) return bad("too many tokens per microbatch");
+  return true;
+}
+
+// Lays the stage out in the arena (or just measures when arena == nullptr).
+size_t layout(zb_stage* st, void* arena) {
+  const zb_config& c = st->cfg;
+  st->L = c.layers; st->h = c.hidden; st->a = c.heads; st->ffn = c.ffn; st->s = c.seq; st->b = c.mb_size;
+  st->T = c.seq * c.mb_size; st->d = c.hidden / c.heads;
+  st->bf16 = c.dtype == ZB_BF16;
+  st->esz = st->bf16 ? 2 : 4;
+  const size_t h = st->h, f = st->ffn, T = st->T;
+  const size_t pc[ZB_P_COUNT] = {h, h, h * 3 * h, 3 * h, h * h, h, h, h, h * f, f, f * h, h};
+  st->poff.assign((size_t)st->L * ZB_P_COUNT, 0);
+  size_t o = 0;
+  for (int l = 0; l < st->L; ++l)
+    for (int i = 0; i < ZB_P_COUNT; ++i) {
+      st->pcount[i] = pc[i];
+      st->poff[l * ZB_P_COUNT + i] = o;
+      o += align_up(pc[i], 64);
+    }
+  st->flat_count = o;
+
+  Bump bp(arena);
+  const size_t fb = o * sizeof(float);
+  st->theta = bp.take<float>(fb);
+  st->grad = bp.take<float>(fb);
+  st->adam_m = bp.take<float>(fb);
+  st->adam_v = bp.take<float>(fb);
+  if (c.journal) {
+    st->j_theta = bp.take<float>(fb);
+    st->j_m = bp.take<float>(fb);
+    st->j_v = bp.take<float>(fb);
+  }
+  if (st->bf16) st->theta16 = bp.take<bf16_t>(o * sizeof(bf16_t));
+
+  const size_t E = st->esz;
+  st->act_bytes = align_up(T * h * E);
+  const size_t io = st->act_bytes * (size_t)c.max_microbatches;
+  st->in_x = bp.take<char>(io);
+  st->in_dy = bp.take<char>(io);
+  st->out_y = bp.take<char>(io);
+  st->out_dx = bp.take<char>(io);
+
+  st->lo.assign(st->L, LayerOff());
+  size_t ofb = 0, ofw = 0, obw = 0;
+  auto put = [&](size_t& cur, size_t bytes) { size_t p = cur; cur += align_up(bytes); return p; };
+  for (int l = 0; l < st->L; ++l) {
+    LayerOff& q = st->lo[l];
+    q.fb_x = put(ofb, l == 0 ? 0 : T * h * E);
+    q.fb_qkv = put(ofb, T * 3 * h * E);
+    q.fb_y1 = put(ofb, T * h * E);
+    q.fb_fh = put(ofb, T * f * E);
+    q.fb_stats1 = put(ofb, T * 2 * sizeof(float));
+    q.fb_stats2 = put(ofb, T * 2 * sizeof(float));
+    q.fb_lse = put(ofb, (size_t)st->b * st->a * st->s * sizeof(float));
+    q.fw_a = put(ofw, T * h * E);
+    q.fw_c = put(ofw, T * h * E);
+    q.fw_u = put(ofw, T * h * E);
+    q.fw_g = put(ofw, T * f * E);
+    q.bw_dqkv = put(obw, T * 3 * h * E);
+    q.bw_dy1 = put(obw, T * h * E);
+    q.bw_dfh = put(obw, T * f * E);
+    q.bw_dy = put(obw, l == st->L - 1 ? 0 : T * h * E);
+  }
+  st->fb_slot = ofb; st->fw_slot = ofw; st->bw_slot = obw;
+  st->fb_pool = bp.take<char>(ofb * (size_t)c.max_pending_b);
+  st->fw_pool = bp.take<char>(ofw * (size_t)c.max_inflight);
+  st->bw_pool = bp.take<char>(obw * (size_t)c.max_pending_w);
+
+  st->tmp = bp.take<char>(T * h * E);
+  st->dvec = bp.take<float>((size_t)st->b * st->a * st->s * sizeof(float));
+  st->ln_partials = bp.take<float>((size_t)kLnBwdBlocks * 2 * h * sizeof(float));
+  size_t stg = h * f;
+  if (h * 3 * h > stg) stg = h * 3 * h;
+  if (T * h > stg) stg = T * h;
+  st->staging_floats = stg;
+  st->staging = bp.take<float>(stg * sizeof(float));
+  st->partial_sq = bp.take<double>(kSumsqBlocks * sizeof(double));
+  st->partial_nf = bp.take<int>(kSumsqBlocks * sizeof(int));
+  st->opt = bp.take<OptDevState>(sizeof(OptDevState));
+  return align_up(bp.off);
+}
+
+void order_shape(int p, int sigma, int m, int kind, int* w, int* delta) {
+  const int base = p - 1 - sigma;
+  if (kind == ZB_H2) {
+    *w = 2 * base < m ? 2 * base : m;
+    *delta = 2 * sigma < m ? 2 * sigma : m;
+  } else {
+    *w = base < m ? base : m;
+    *delta = kind == ZB_H1 ? (sigma < m ? sigma : m) : 0;
+  }
+}
+
+zb_status check_sched_args(int p, int stage, int m, int kind) {
+  if (p < 1 || stage < 0 || stage >= p || m < 1 || m > (1 << 20)) return ZB_EINVAL;
+  if (kind != ZB_1F1B && kind != ZB_H1 && kind != ZB_H2) return ZB_EINVAL;
+  return ZB_OK;
+}
+
+// Warm-up forwards, then (F, B, deferred W) triples, then the W tail.
+void build_order(int p, int sigma, int m, int kind, std::vector<zb_op>* out) {
+  int w, delta;
+  order_shape(p, sigma, m, kind, &w, &delta);
+  out->clear();
+  out->reserve(3 * (size_t)m);
+  for (int k = 0; k < w; ++k) out->push_back({ZB_PASS_F, k});
+  for (int k = 0; k < m; ++k) {
+    if (w + k < m) out->push_back({ZB_PASS_F, w + k});
+    out->push_back({ZB_PASS_B, k});
+    if (k >= delta) out->push_back({ZB_PASS_W, k - delta});
+  }
+  for (int k = m - delta; k < m; ++k) out->push_back({ZB_PASS_W, k});
+}
+
+template <typename T> struct Exec {
+  static hipError_t gemm(zb_stage* st, int cls, const GemmArgs& g) {
+    double bytes = 0;
+    const double E = sizeof(T);
+    if (g.epilogue == EPI_ACCUM_F32) bytes = 8.0 * g.M * g.N + E * (double)g.K * ((double)g.M + g.N);
+    else bytes = E * ((double)g.M * g.K + (double)g.K * g.N + (double)g.M * g.N);
+    ProfScope ps(st, cls, 2.0 * g.M * g.N * g.K, bytes);
+    return launch_gemm<T>(g, st->stream);
+  }
+
+  static zb_status forward(zb_stage* st, int mb) {
+    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    hipStream_t s = st->stream;
+    char* fb = st->fb_pool + st->fb_slot * (size_t)st->slot_fb[mb];
+    char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
+    const T* x = (const T*)(st->in_x + st->act_bytes * (size_t)mb);
+    const double E = sizeof(T);
+    for (int l = 0; l < L; ++l) {
+      const LayerOff& q = st->lo[l];
+      T* A = (T*)(fw + q.fw_a);
+      T* C = (T*)(fw + q.fw_c);
+      T* U = (T*)(fw + q.fw_u);
+      T* Gl = (T*)(fw + q.fw_g);
+      T* QKV = (T*)(fb + q.fb_qkv);
+      T* Y1 = (T*)(fb + q.fb_y1);
+      T* Fh = (T*)(fb + q.fb_fh);
+      float* st1 = (float*)(fb + q.fb_stats1);
+      float* st2 = (float*)(fb + q.fb_stats2);
+      float* lse = (float*)(fb + q.fb_lse);
+      T* y = (l == L - 1) ? (T*)(st->out_y + st->act_bytes * (size_t)mb) : (T*)(fb + st->lo[l + 1].fb_x);
+      {
+        ProfScope ps(st, KC_LN_FWD, 0, 2 * E * T_ * h + 8.0 * T_);
+        ZB_HIP(st, launch_layernorm_fwd<T>(x, st->P(l, ZB_P_LN1_G), st->P(l, ZB_P_LN1_B), A, st1, T_, h,
+                                            st->cfg.ln_eps, s));
+      }
+      GemmArgs g{};
+      g.A = A; g.B = st->Wt(l, ZB_P_WQKV); g.M = T_; g.N = 3 * h; g.K = h;
+      g.a_sm = h; g.a_sk = 1; g.b_sk = 3 * h; g.b_sn = 1;
+      g.epilogue = EPI_BIAS; g.out0 = QKV; g.bias = st->P(l, ZB_P_BQKV);
+      ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
+      {
+        AttnArgs aa{};
+        aa.qkv = QKV; aa.out = C; aa.lse = lse; aa.b = st->b; aa.s = st->s; aa.a = st->a; aa.d = st->d;
+        ProfScope ps(st, KC_ATTN_FWD, 4.0 * st->s * (double)st->s * st->b * h, E * 4.0 * T_ * h);
+        ZB_HIP(st, launch_attention_fwd<T>(aa, s));
+      }
+      g = GemmArgs{};
+      g.A = C; g.B = st->Wt(l, ZB_P_WO); g.M = T_; g.N = h; g.K = h;
+      g.a_sm = h; g.a_sk = 1; g.b_sk = h; g.b_sn = 1;
+      g.epilogue = EPI_BIAS_RESID; g.out0 = Y1; g.bias = st->P(l, ZB_P_BO); g.aux = x;
+      ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
+      {
+        ProfScope ps(st, KC_LN_FWD, 0, 2 * E * T_ * h + 8.0 * T_);
+        ZB_HIP(st, launch_layernorm_fwd<T>(Y1, st->P(l, ZB_P_LN2_G), st->P(l, ZB_P_LN2_B), U, st2, T_, h,
+                                            st->cfg.ln_eps, s));
+      }
+      g = GemmArgs{};
+      g.A = U; g.B = st->Wt(l, ZB_P_W1); g.M = T_; g.N = f; g.K = h;
+      g.a_sm = h; g.a_sk = 1; g.b_sk = f; g.b_sn = 1;
+      g.epilogue = EPI_BIAS_GELU; g.out0 = Fh; g.out1 = Gl; g.bias = st->P(l, ZB_P_B1);
+      ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
+      g = GemmArgs{};
+      g.A = Gl; g.B = st->Wt(l, ZB_P_W2); g.M = T_; g.N = h; g.K = f;
+      g.a_sm = f; g.a_sk = 1; g.b_sk = h; g.b_sn = 1;
+      g.epilogue = EPI_BIAS_RESID; g.out0 = y; g.bias = st->P(l, ZB_P_B2); g.aux = Y1;
+      ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
+      x = y;
+    }
+    return ZB_OK;
+  }
+
+  static zb_status backward_input(zb_stage* st, int mb) {
+    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    hipStream_t s = st->stream;
+    char* fb = st->fb_pool + st->fb_slot * (size_t)st->slot_fb[mb];
+    char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
+    char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
+    const T* dy = (const T*)(st->in_dy + st->act_bytes * (size_t)mb);
+    T* tmp = (T*)st->tmp;
+    const double E = sizeof(T);
+    for (int l = L - 1; l >= 0; --l) {
+      const LayerOff& q = st->lo[l];
+      const T* xl = l == 0 ? (const T*)(st->in_x + st->act_bytes * (size_t)mb) : (const T*)(fb + q.fb_x);
+      const T* QKV = (const T*)(fb + q.fb_qkv);
+      const T* Y1 = (const T*)(fb + q.fb_y1);
+      const T* Fh = (const T*)(fb + q.fb_fh);
+      const float* st1 = (const float*)(fb + q.fb_stats1);
+      const float* st2 = (const float*)(fb + q.fb_stats2);
+      float* lse = (float*)(fb + q.fb_lse);
+      const T* C = (const T*)(fw + q.fw_c);
+      T* dQKV = (T*)(bw + q.bw_dqkv);
+      T* dY1 = (T*)(bw + q.bw_dy1);
+      T* dFh = (T*)(bw + q.bw_dfh);
+      T* dx = l == 0 ? (T*)(st->out_dx + st->act_bytes * (size_t)mb) : (T*)(bw + st->lo[l - 1].bw_dy);
+
+      GemmArgs g{};  // dFh = (dY W2^T) * gelu'(Fh)
+      g.A = dy; g.B = st->Wt(l, ZB_P_W2); g.M = T_; g.N = f; g.K = h;
+      g.a_sm = h; g.a_sk = 1; g.b_sk = 1; g.b_sn = h;
+      g.epilogue = EPI_DGELU; g.out0 = dFh; g.aux = Fh;
+      ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
+      g = GemmArgs{};  // dU = dFh W1^T
+      g.A = dFh; g.B = st->Wt(l, ZB_P_W1); g.M = T_; g.N = h; g.K = f;
+      g.a_sm = f; g.a_sk = 1; g.b_sk = 1; g.b_sn = f;
+      g.epilogue = EPI_STORE; g.out0 = tmp;
+      ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
+      {
+        ProfScope ps(st, KC_LN_BWD, 0, 4 * E * T_ * h);
+        ZB_HIP(st, launch_layernorm_bwd<T>(tmp, Y1, st2, st->P(l, ZB_P_LN2_G), dy, dY1, st->G(l, ZB_P_LN2_G),
+                                            st->G(l, ZB_P_LN2_B), st->ln_partials, T_, h, s));
+      }
+      g = GemmArgs{};  // dC = dY1 Wo^T
+      g.A = dY1; g.B = st->Wt(l, ZB_P_WO); g.M = T_; g.N = h; g.K = h;
+      g.a_sm = h; g.a_sk = 1; g.b_sk = 1; g.b_sn = h;
+      g.epilogue = EPI_STORE; g.out0 = tmp;
+      ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
+      {
+        AttnArgs aa{};
+        aa.qkv = QKV; aa.o = C; aa.dout = tmp; aa.lse = lse; aa.dqkv = dQKV; aa.dvec = st->dvec;
+        aa.b = st->b; aa.s = st->s; aa.a = st->a; aa.d = st->d;
+        ProfScope ps(st, KC_ATTN_BWD, 8.0 * st->s * (double)st->s * st->b * h, E * 8.0 * T_ * h);
+        ZB_HIP(st, launch_attention_bwd<T>(aa, s));
+      }
+      g = GemmArgs{};  // dA = dQKV Wqkv^T
+      g.A = dQKV; g.B = st->Wt(l, ZB_P_WQKV); g.M = T_; g.N = h; g.K = 3 * h;
+      g.a_sm = 3 * h; g.a_sk = 1; g.b_sk = 1; g.b_sn = 3 * h;
+      g.epilogue = EPI_STORE; g.out0 = tmp;
+      ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
+      {
+        ProfScope ps(st, KC_LN_BWD, 0, 4 * E * T_ * h);
+        ZB_HIP(st, launch_layernorm_bwd<T>(tmp, xl, st1, st->P(l, ZB_P_LN1_G), dY1, dx, st->G(l, ZB_P_LN1_G),
+                                            st->G(l, ZB_P_LN1_B), st->ln_partials, T_, h, s));
+      }
+      dy = dx;
+    }
+    return ZB_OK;
+  }
+
+  static zb_status backward_weight(zb_stage* st, int mb) {
+    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    hipStream_t s = st->stream;
+    char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
+    char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
+    const double E = sizeof(T);
+    for (int l = L - 1; l >= 0; --l) {
+      const LayerOff& q = st->lo[l];
+      const T* dyl = l == L - 1 ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
+      struct Pair { const T* x; const T* dy; int kin, nout, wi, bi; };
+      const Pair pairs[4] = {
+          {(const T*)(fw + q.fw_g), dyl, f, h, ZB_P_W2, ZB_P_B2},
+          {(const T*)(fw + q.fw_u), (const T*)(bw + q.bw_dfh), h, f, ZB_P_W1, ZB_P_B1},
+          {(const T*)(fw + q.fw_c), (const T*)(bw + q.bw_dy1), h, h, ZB_P_WO, ZB_P_BO},
+          {(const T*)(fw + q.fw_a), (const T*)(bw + q.bw_dqkv), h, 3 * h, ZB_P_WQKV, ZB_P_BQKV}};
+      for (const Pair& pr : pairs) {
+        GemmArgs g{};  // dW[kin, nout] += X^T dY
+        g.A = pr.x; g.B = pr.dy; g.M = pr.kin; g.N = pr.nout; g.K = T_;
+        g.a_sm = 1; g.a_sk = pr.kin; g.b_sk = pr.nout; g.b_sn = 1;
+        g.epilogue = EPI_ACCUM_F32; g.outf = st->G(l, pr.wi);
+        ZB_HIP(st, gemm(st, KC_GEMM_WGRAD, g));
+        ProfScope ps(st, KC_COLSUM, 0, E * T_ * pr.nout);
+        ZB_HIP(st, launch_colsum_accum<T>(pr.dy, st->G(l, pr.bi), T_, pr.nout, s));
+      }
+    }
+    return ZB_OK;
+  }
+};
+
+zb_status check_pass(zb_stage* st, int pass, int mb) {
+  if (!st) return ZB_EINVAL;
+  st->err.clear();
+  if (st->m <= 0) return fail(st, ZB_ESTATE, "zb_begin_iteration has not been called");
+  if (mb < 0 || mb >= st->m) return fail(st, ZB_EINVAL, "microbatch index out of range");
+  if (st->done[pass][mb]) return fail(st, ZB_EORDER, "pass already run for this microbatch in this iteration");
+  if (pass == ZB_PASS_B && !st->done[ZB_PASS_F][mb]) return fail(st, ZB_EORDER, "B before F of the same microbatch");
+  if (pass == ZB_PASS_W && !st->done[ZB_PASS_B][mb]) return fail(st, ZB_EORDER, "W before B of the same microbatch");
+  return ZB_OK;
+}
+
+int take_slot(std::vector<int>& pool) {
+  if (pool.empty()) return -1;
+  int v = pool.back();
+  pool.pop_back();
+  return v;
+}
+
+struct TensorRef {
+  bool typed;      // true: stored in the stage's data type; false: fp32
+  void* ptr;
+  size_t count;
+  bool writable;
+  bool is_param;   // also refresh the bf16 working copy
+  size_t flat_off;
+};
+
+zb_status resolve(zb_stage* st, int what, int layer, int mb, TensorRef* r) {
+  *r = TensorRef{};
+  r->writable = true;
+  if (what >= ZB_T_PARAM && what < ZB_T_ADAM_V + 16) {
+    const int grp = what / 16, i = what % 16;
+    if (i >= ZB_P_COUNT) return fail(st, ZB_EINVAL, "bad parameter index");
+    if (layer < 0 || layer >= st->L) return fail(st, ZB_EINVAL, "layer out of range");
+    float* base = grp == 0 ? st->theta : grp == 1 ? st->grad : grp == 2 ? st->adam_m : st->adam_v;
+    r->typed = false;
+    r->flat_off = st->poff[layer * ZB_P_COUNT + i];
+    r->ptr = base + r->flat_off;
+    r->count = st->pcount[i];
+    r->is_param = grp == 0;
+    return ZB_OK;
+  }
+  if (what >= ZB_T_INPUT_X && what <= ZB_T_OUTPUT_DX) {
+    if (mb < 0 || mb >= st->cfg.max_microbatches) return fail(st, ZB_EINVAL, "microbatch out of range");
+    char* base = what == ZB_T_INPUT_X ? st->in_x : what == ZB_T_INPUT_DY ? st->in_dy
+               : what == ZB_T_OUTPUT_Y ? st->out_y : st->out_dx;
+    r->typed = true;
+    r->ptr = base + st->act_bytes * (size_t)mb;
+    r->count = (size_t)st->T * st->h;
+    r->writable = what == ZB_T_INPUT_X || what == ZB_T_INPUT_DY;
+    return ZB_OK;
+  }
+  if (what >= ZB_T_FLAT_PARAMS && what <= ZB_T_FLAT_ADAM_V) {
+    float* base = what == ZB_T_FLAT_PARAMS ? st->theta : what == ZB_T_FLAT_GRADS ? st->grad
+                : what == ZB_T_FLAT_ADAM_M ? st->adam_m : st->adam_v;
+    r->typed = false;
+    r->ptr = base;
+    r->count = st->flat_count;
+    r->writable = false;
+    return ZB_OK;
+  }
+  return fail(st, ZB_EINVAL, "unknown tensor selector");
+}
+
+}  // namespace
+
+extern "C" {
+
+zb_status zb_config_defaults(zb_config* cfg) {
+  if (!cfg) return ZB_EINVAL;
+  memset(cfg, 0, sizeof(*cfg));
+  cfg->mb_size = 1;
+  cfg->dtype = ZB_BF16;
+  cfg->journal = 1;
+  cfg->ln_eps = 1e-5f;
+  cfg->lr = 1e-4f; cfg->beta1 = 0.9f; cfg->beta2 = 0.95f; cfg->adam_eps = 1e-8f; cfg->weight_decay = 0.01f;
+  cfg->clip = 1.0f;
+  return ZB_OK;
+}
+
+zb_status zb_stage_arena_bytes(const zb_config* cfg, size_t* bytes) {
+  std::string why;
+  if (!bytes || !valid_shapes(cfg, &why)) return ZB_EINVAL;
+  zb_stage tmp;
+  tmp.cfg = *cfg;
+  *bytes = layout(&tmp, nullptr);
+  return ZB_OK;
+}
+
+zb_status zb_stage_init(const zb_config* cfg, zb_stage** out) {
+  if (!out) return ZB_EINVAL;
+  *out = nullptr;
+  std::string why;
+  if (!valid_shapes(cfg, &why)) return ZB_EINVAL;
+  if (!cfg->arena || (reinterpret_cast<uintptr_t>(cfg->arena) & (kAlign - 1))) return ZB_EINVAL;
+  if (!(cfg->beta1 > 0.f && cfg->beta1 < 1.f && cfg->beta2 > 0.f && cfg->beta2 < 1.f)) return ZB_EINVAL;
+  zb_stage* st = new (std::nothrow) zb_stage();
+  if (!st) return ZB_ENOMEM;
+  st->cfg = *cfg;
+  const size_t need = layout(st, cfg->arena);
+  if (need > cfg->arena_bytes) {
+    delete st;
+    return ZB_ENOMEM;
+  }
+  st->stream = (hipStream_t)cfg->hip_stream;
+  st->hp = OptHyper{cfg->lr, cfg->beta1, cfg->beta2, cfg->adam_eps, cfg->weight_decay, cfg->clip};
+  for (int i = 0; i < KC_COUNT; ++i) st->prof_flops[i] = st->prof_bytes[i] = 0;
+  // zero state: parameters, moments, gradients, journal, optimizer scalars
+  hipError_t e = hipMemsetAsync(cfg->arena, 0, need, st->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(st->stream);
+  if (e != hipSuccess) {
+    delete st;
+    return ZB_EDEVICE;
+  }
+  st->slot_fb.assign(cfg->max_microbatches, -1);
+  st->slot_fw.assign(cfg->max_microbatches, -1);
+  st->slot_bw.assign(cfg->max_microbatches, -1);
+  *out = st;
+  return ZB_OK;
+}
+
+zb_status zb_stage_free(zb_stage* st) {
+  if (!st) return ZB_EINVAL;
+  (void)hipStreamSynchronize(st->stream);
+  for (auto& r : st->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : st->ev_pool) (void)hipEventDestroy(e);
+  delete st;
+  return ZB_OK;
+}
+
+zb_status zb_stage_flat_count(const zb_stage* st, size_t* count) {
+  if (!st || !count) return ZB_EINVAL;
+  *count = st->flat_count;
+  return ZB_OK;
+}
+
+zb_status zb_begin_iteration(zb_stage* st, int32_t iter, int32_t m) {
+  if (!st) return ZB_EINVAL;
+  st->err.clear();
+  if (m < 1 || m > st->cfg.max_microbatches) return fail(st, ZB_EINVAL, "m must be in [1, max_microbatches]");
+  st->m = m;
+  st->iter = iter;
+  for (int c = 0; c < 3; ++c) st->done[c].assign(m, 0);
+  st->free_fb.clear(); st->free_fw.clear(); st->free_bw.clear();
+  for (int i = st->cfg.max_pending_b - 1; i >= 0; --i) st->free_fb.push_back(i);
+  for (int i = st->cfg.max_inflight - 1; i >= 0; --i) st->free_fw.push_back(i);
+  for (int i = st->cfg.max_pending_w - 1; i >= 0; --i) st->free_bw.push_back(i);
+  ProfScope ps(st, KC_FILL, 0, 4.0 * st->flat_count);
+  ZB_HIP(st, launch_fill_f32(st->grad, st->flat_count, 0.f, st->stream));
+  return ZB_OK;
+}
+
+zb_status zb_forward(zb_stage* st, int32_t mb) {
+  zb_status rc = check_pass(st, ZB_PASS_F, mb);
+  if (rc != ZB_OK) return rc;
+  if (st->free_fb.empty() || st->free_fw.empty())
+    return fail(st, ZB_ENOMEM, "no free stash slot for F: raise max_pending_b / max_inflight");
+  st->slot_fb[mb] = take_slot(st->free_fb);
+  st->slot_fw[mb] = take_slot(st->free_fw);
+  rc = st->bf16 ? Exec<bf16_t>::forward(st, mb) : Exec<float>::forward(st, mb);
+  if (rc != ZB_OK) return rc;
+  st->done[ZB_PASS_F][mb] = 1;
+  return ZB_OK;
+}
+
+zb_status zb_backward_input(zb_stage* st, int32_t mb) {
+  zb_status rc = check_pass(st, ZB_PASS_B, mb);
+  if (rc != ZB_OK) return rc;
+  if (st->free_bw.empty()) return fail(st, ZB_ENOMEM, "no free stash slot for B: raise max_pending_w");
+  st->slot_bw[mb] = take_slot(st->free_bw);
+  rc = st->bf16 ? Exec<bf16_t>::backward_input(st, mb) : Exec<float>::backward_input(st, mb);
+  if (rc != ZB_OK) return rc;
+  st->done[ZB_PASS_B][mb] = 1;
+  st->free_fb.push_back(st->slot_fb[mb]);  // what only B needed is released (stream order keeps it safe)
+  st->slot_fb[mb] = -1;
+  return ZB_OK;
+}
+
+zb_status zb_backward_weight(zb_stage* st, int32_t mb) {
+  zb_status rc = check_pass(st, ZB_PASS_W, mb);
+  if (rc != ZB_OK) return rc;
+  rc = st->bf16 ? Exec<bf16_t>::backward_weight(st, mb) : Exec<float>::backward_weight(st, mb);
+  if (rc != ZB_OK) return rc;
+  st->done[ZB_PASS_W][mb] = 1;
+  st->free_fw.push_back(st->slot_fw[mb]);
+  st->free_bw.push_back(st->slot_bw[mb]);
+  st->slot_fw[mb] = st->slot_bw[mb] = -1;
+  return ZB_OK;
+}
+
+zb_status zb_schedule_order(int32_t p, int32_t stage, int32_t m, int32_t kind, zb_op* out, int32_t cap,
+                            int32_t* n) {
+  if (!n || check_sched_args(p, stage, m, kind) != ZB_OK) return ZB_EINVAL;
+  *n = 3 * m;
+  if (!out || cap < 3 * m) return ZB_EINVAL;
+  std::vector<zb_op> ops;
+  build_order(p, stage, m, kind, &ops);
+  memcpy(out, ops.data(), ops.size() * sizeof(zb_op));
+  return ZB_OK;
+}
+
+zb_status zb_schedule_stash_need(int32_t p, int32_t stage, int32_t m, int32_t kind, int32_t* max_pending_b,
+                                 int32_t* max_pending_w, int32_t* max_inflight) {
+  if (check_sched_args(p, stage, m, kind) != ZB_OK) return ZB_EINVAL;
+  std::vector<zb_op> ops;
+  build_order(p, stage, m, kind, &ops);
+  int nb = 0, nw = 0, mb_ = 0, mw_ = 0, mi_ = 0;
+  for (const zb_op& op : ops) {
+    if (op.pass == ZB_PASS_F) ++nb;
+    else if (op.pass == ZB_PASS_B) { --nb; ++nw; }
+    else --nw;
+    if (nb > mb_) mb_ = nb;
+    if (nw > mw_) mw_ = nw;
+    if (nb + nw > mi_) mi_ = nb + nw;
+  }
+  if (max_pending_b) *max_pending_b = mb_;
+  if (max_pending_w) *max_pending_w = mw_;
+  if (max_inflight) *max_inflight = mi_;
+  return ZB_OK;
+}
+
+zb_status zb_run_schedule(zb_stage* st, int32_t p, int32_t stage, int32_t m, int32_t kind) {
+  if (!st) return ZB_EINVAL;
+  st->err.clear();
+  if (check_sched_args(p, stage, m, kind) != ZB_OK) return fail(st, ZB_EINVAL, "bad schedule arguments");
+  if (m != st->m) return fail(st, ZB_ESTATE, "m differs from zb_begin_iteration's");
+  std::vector<zb_op> ops;
+  build_order(p, stage, m, kind, &ops);
+  for (const zb_op& op : ops) {
+    zb_status rc = op.pass == ZB_PASS_F ? zb_forward(st, op.mb)
+                 : op.pass == ZB_PASS_B ? zb_backward_input(st, op.mb) : zb_backward_weight(st, op.mb);
+    if (rc != ZB_OK) return rc;
+  }
+  return ZB_OK;
+}
+
+zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, zb_step_report* report) {
+  if (!st || !gs) return ZB_EINVAL;
+  st->err.clear();
+  if (!(gs->prev_sq >= 0.0) && !isnan(gs->prev_sq)) return fail(st, ZB_EINVAL, "prev_sq must not be negative");
+  if (!(gs->rest_sq >= 0.0) && !isnan(gs->rest_sq)) return fail(st, ZB_EINVAL, "rest_sq must not be negative");
+  hipStream_t s = st->stream;
+  const size_t n = st->flat_count;
+  const double n_d = (double)n;
+  const int prev_nf = gs->prev_nonfinite ? 1 : 0, rest_nf = gs->rest_nonfinite ? 1 : 0;
+  const double step_bytes = n_d * (16 + 12 + (st->j_theta ? 12 : 0) + (st->theta16 ? 2 : 0));
+  {  // local state of this stage
+    ProfScope ps(st, KC_SUMSQ, 0, 4.0 * n_d);
+    ZB_HIP(st, launch_grad_sumsq(st->grad, n, st->partial_sq, st->partial_nf, st->opt, s));
+  }
+  // optimistic step controlled by the partially reduced state
+  ZB_HIP(st, launch_decide_optimistic(st->opt, st->hp, gs->prev_sq, prev_nf, gs->force_optimistic ? 1 : 0, s));
+  {
+    ProfScope ps(st, KC_ADAMW_STEP, 0, step_bytes);
+    ZB_HIP(st, launch_adamw_step(st->theta, st->adam_m, st->adam_v, st->grad, st->j_theta, st->j_m, st->j_v,
+                                 st->theta16, n, st->hp, st->opt, s));
+  }
+  // validation against the fully reduced state; rollback and redo if the step was not legitimate
+  ZB_HIP(st, launch_decide_validate(st->opt, st->hp, gs->prev_sq, gs->rest_sq, prev_nf, rest_nf, s));
+  {
+    ProfScope ps(st, KC_ADAMW_ROLLBACK, 0, n_d * (16 + 12 + (st->j_theta ? 12 : 0) + (st->theta16 ? 2 : 0)));
+    ZB_HIP(st, launch_adamw_rollback(st->theta, st->adam_m, st->adam_v, st->grad, st->j_theta, st->j_m, st->j_v,
+                                     st->theta16, n, st->hp, st->opt, s));
+  }
+  ZB_HIP(st, launch_decide_after_rollback(st->opt, st->hp, s));
+  {
+    ProfScope ps(st, KC_ADAMW_STEP, 0, step_bytes);
+    ZB_HIP(st, launch_adamw_step(st->theta, st->adam_m, st->adam_v, st->grad, st->j_theta, st->j_m, st->j_v,
+                                 st->theta16, n, st->hp, st->opt, s));
+  }
+  ZB_HIP(st, launch_clear_step(st->opt, s));
+  if (report) {
+    OptDevState h;
+    ZB_HIP(st, hipMemcpyAsync(&h, st->opt, sizeof(h), hipMemcpyDeviceToHost, s));
+    ZB_HIP(st, hipStreamSynchronize(s));
+    report->outcome = h.outcome;
+    report->stepped_optimistically = h.stepped;
+    report->local_sq = h.local_sq;
+    report->global_norm = h.global_norm;
+    report->clip_coef = h.clip_coef;
+    report->t = h.t;
+    report->alg1_mismatch_elems = h.mismatch;
+  }
+  return ZB_OK;
+}
+
+zb_status zb_get_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, void* host_dst, size_t bytes) {
+  if (!st || !host_dst) return ZB_EINVAL;
+  st->err.clear();
+  TensorRef r;
+  zb_status rc = resolve(st, what, layer, mb, &r);
+  if (rc != ZB_OK) return rc;
+  if (bytes != r.count * sizeof(float)) return fail(st, ZB_EINVAL, "bytes must be 4 * element count");
+  hipStream_t s = st->stream;
+  const void* src = r.ptr;
+  if (r.typed && st->bf16) {
+    if (r.count > st->staging_floats) return fail(st, ZB_ESTATE, "staging buffer too small");
+    ZB_HIP(st, launch_convert_to_f32<bf16_t>((const bf16_t*)r.ptr, st->staging, r.count, s));
+    src = st->staging;
+  }
+  ZB_HIP(st, hipMemcpyAsync(host_dst, src, bytes, hipMemcpyDeviceToHost, s));
+  ZB_HIP(st, hipStreamSynchronize(s));
+  return ZB_OK;
+}
+
+zb_status zb_set_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, const void* host_src, size_t bytes) {
+  if (!st || !host_src) return ZB_EINVAL;
+  st->err.clear();
+  TensorRef r;
+  zb_status rc = resolve(st, what, layer, mb, &r);
+  if (rc != ZB_OK) return rc;
+  if (!r.writable) return fail(st, ZB_EINVAL, "tensor is read-only");
+  if (bytes != r.count * sizeof(float)) return fail(st, ZB_EINVAL, "bytes must be 4 * element count");
+  hipStream_t s = st->stream;
+  if (r.typed && st->bf16) {
+    if (r.count > st->staging_floats) return fail(st, ZB_ESTATE, "staging buffer too small");
+    ZB_HIP(st, hipMemcpyAsync(st->staging, host_src, bytes, hipMemcpyHostToDevice, s));
+    ZB_HIP(st, launch_convert_from_f32<bf16_t>(st->staging, (bf16_t*)r.ptr, r.count, s));
+  } else {
+    ZB_HIP(st, hipMemcpyAsync(r.ptr, host_src, bytes, hipMemcpyHostToDevice, s));
+    if (r.is_param && st->bf16)
+      ZB_HIP(st, launch_convert_from_f32<bf16_t>((const float*)r.ptr, st->theta16 + r.flat_off, r.count, s));
+  }
+  ZB_HIP(st, hipStreamSynchronize(s));
+  return ZB_OK;
+}
+
+zb_status zb_inject(zb_stage* st, int32_t what, int32_t mb, int64_t elem, float value) {
+  if (!st) return ZB_EINVAL;
+  st->err.clear();
+  if (what != ZB_T_INPUT_X && what != ZB_T_INPUT_DY) return fail(st, ZB_EINVAL, "only inputs can be injected");
+  TensorRef r;
+  zb_status rc = resolve(st, what, 0, mb, &r);
+  if (rc != ZB_OK) return rc;
+  if (elem < 0 || (size_t)elem >= r.count) return fail(st, ZB_EINVAL, "element out of range");
+  if (st->bf16) ZB_HIP(st, launch_poke<bf16_t>((bf16_t*)r.ptr, (size_t)elem, value, st->stream));
+  else ZB_HIP(st, launch_poke<float>((float*)r.ptr, (size_t)elem, value, st->stream));
+  return ZB_OK;
+}
+
+zb_status zb_synchronize(zb_stage* st) {
+  if (!st) return ZB_EINVAL;
+  st->err.clear();
+  ZB_HIP(st, hipStreamSynchronize(st->stream));
+  return ZB_OK;
+}
+
+const char* zb_last_error(const zb_stage* st) { return st ? st->err.c_str() : "null stage"; }
+
+zb_status zb_stage_model_flops(const zb_stage* st, int32_t m, double* flops) {
+  if (!st || !flops || m < 0) return ZB_EINVAL;
+  const double s = st->s, b = st->b, h = st->h;
+  const double F = s * b * h * (24 * h + 4 * s), B = s * b * h * (24 * h + 8 * s), W = s * b * h * 24 * h;
+  *flops = (double)st->L * m * (F + B + W);
+  return ZB_OK;
+}
+
+zb_status zb_profile_enable(zb_stage* st, int32_t on) {
+  if (!st) return ZB_EINVAL;
+  st->err.clear();
+  ZB_HIP(st, hipStreamSynchronize(st->stream));
+  if (on) {
+    for (auto& r : st->prof) { st->ev_pool.push_back(r.a); st->ev_pool.push_back(r.b); }
+    st->prof.clear();
+    for (int i = 0; i < KC_COUNT; ++i) st->prof_flops[i] = st->prof_bytes[i] = 0;
+  }
+  st->profiling = on != 0;
+  return ZB_OK;
+}
+
+zb_status zb_profile_read(zb_stage* st, zb_kernel_stat* out, int32_t cap, int32_t* n) {
+  if (!st || !n) return ZB_EINVAL;
+  st->err.clear();
+  ZB_HIP(st, hipStreamSynchronize(st->stream));
+  double ms[KC_COUNT] = {0};
+  long long cnt[KC_COUNT] = {0};
+  for (const ProfRec& r : st->prof) {
+    float t = 0.f;
+    ZB_HIP(st, hipEventElapsedTime(&t, r.a, r.b));
+    ms[r.cls] += t;
+    cnt[r.cls] += 1;
+  }
+  int k = 0;
+  for (int c = 0; c < KC_COUNT; ++c) {
+    if (!cnt[c]) continue;
+    if (out && k < cap) {
+      memset(&out[k], 0, sizeof(out[k]));
+      snprintf(out[k].name, sizeof(out[k].name), "%s", kClassNames[c]);
+      out[k].launches = cnt[c];
+      out[k].total_ms = ms[c];
+      out[k].flops = st->prof_flops[c];
+      out[k].bytes = st->prof_bytes[c];
+    }
+    ++k;
+  }
+  *n = k;
+  return (out && k > cap) ? ZB_EINVAL : ZB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,157 @@
+// Shared device helpers and launch declarations of the zero-bubble stage library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace zb {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// tanh-form GELU and its derivative (fp32)
+__device__ __forceinline__ float gelu_f(float x) {
+  const float c = 0.7978845608028654f, a = 0.044715f;
+  float u = c * (x + a * x * x * x);
+  return 0.5f * x * (1.0f + tanhf(u));
+}
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  const float c = 0.7978845608028654f, a = 0.044715f;
+  float t = tanhf(c * (x + a * x * x * x));
+  return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * c * (1.0f + 3.0f * a * x * x);
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM:  C[M,N] (op)= sum_k A(m,k) * B(k,n).   A element (m,k) sits at A[m*a_sm + k*a_sk],
+// B element (k,n) at B[k*b_sk + n*b_sn]; exactly one stride of each operand is 1.
+// ---------------------------------------------------------------------------------------
+enum Epilogue : int {
+  EPI_STORE = 0,       // out0 = acc
+  EPI_BIAS = 1,        // out0 = acc + bias[n]
+  EPI_BIAS_RESID = 2,  // out0 = acc + bias[n] + resid[m,n]
+  EPI_BIAS_GELU = 3,   // out0 = acc + bias[n]; out1 = gelu(out0)
+  EPI_DGELU = 4,       // out0 = acc * gelu'(aux[m,n])
+  EPI_ACCUM_F32 = 5    // outf[m,n] += acc   (fp32 gradient accumulation)
+};
+
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  int M, N, K;
+  long a_sm, a_sk, b_sk, b_sn;
+  int epilogue;
+  void* out0;          // [M,N] row-major, element type T
+  void* out1;          // second output (EPI_BIAS_GELU)
+  float* outf;         // fp32 [M,N] (EPI_ACCUM_F32)
+  const float* bias;   // [N] fp32
+  const void* aux;     // resid or pre-activation, [M,N] type T
+};
+
+template <typename T> hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// attention (causal, per head), token-major QKV [tokens, 3h] with columns [Q|K|V] head-major
+// ---------------------------------------------------------------------------------------
+struct AttnArgs {
+  const void* qkv;   // [b*s, 3h]
+  void* out;         // fwd: C [b*s, h]
+  float* lse;        // [b, a, s] log-sum-exp of the scaled, masked scores
+  const void* dout;  // bwd: dC [b*s, h]
+  const void* o;     // bwd: C
+  void* dqkv;        // bwd: [b*s, 3h]
+  float* dvec;       // bwd scratch [b, a, s]: rowsum(dO * O)
+  int b, s, a, d;
+};
+template <typename T> hipError_t launch_attention_fwd(const AttnArgs& a, hipStream_t s);
+template <typename T> hipError_t launch_attention_bwd(const AttnArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// row-wise / elementwise
+// ---------------------------------------------------------------------------------------
+template <typename T>
+hipError_t launch_layernorm_fwd(const T* x, const float* gamma, const float* beta, T* out, float* stats,
+                                int rows, int h, float eps, hipStream_t s);
+// dx = resid + LNbwd(g); partial dgamma/dbeta go to `partials` ([blocks][2][h]) and are then
+// added to dgamma/dbeta in a fixed order.  Returns the number of partial blocks via launch.
+template <typename T>
+hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid,
+                                T* dx, float* dgamma, float* dbeta, float* partials, int rows, int h,
+                                hipStream_t s);
+constexpr int kLnBwdBlocks = 128;
+
+// bias gradient: db[n] += sum_rows dy[r, n]
+template <typename T>
+hipError_t launch_colsum_accum(const T* dy, float* db, int rows, int n, hipStream_t s);
+
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
+template <typename T> hipError_t launch_convert_from_f32(const float* src, T* dst, size_t n, hipStream_t s);
+template <typename T> hipError_t launch_convert_to_f32(const T* src, float* dst, size_t n, hipStream_t s);
+template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// optimizer (Sec. 4 and Appendix C).  All decisions live in OptDevState on the device.
+// ---------------------------------------------------------------------------------------
+struct OptDevState {
+  double local_sq;
+  double global_norm;
+  double clip_coef;
+  unsigned long long mismatch;
+  int local_nonfinite;
+  int t;                 // Algorithm 1's time stamp
+  int stepped;           // optimistic step taken
+  int do_step;           // predicate of the next step kernel
+  int do_rollback;       // predicate of the rollback kernel
+  int outcome;
+  float step_coef;       // gradient scale of the next step kernel
+  float bc1, bc2;        // 1 - beta1^t, 1 - beta2^t for the step / rollback at time t
+};
+
+struct OptHyper {
+  float lr, beta1, beta2, eps, weight_decay, clip;
+};
+
+constexpr int kSumsqBlocks = 1024;
+hipError_t launch_grad_sumsq(const float* g, size_t n, double* partial_sq, int* partial_nf,
+                             OptDevState* st, hipStream_t s);
+hipError_t launch_decide_optimistic(OptDevState* st, OptHyper hp, double prev_sq, int prev_nf, int force,
+                                    hipStream_t s);
+hipError_t launch_decide_validate(OptDevState* st, OptHyper hp, double prev_sq, double rest_sq, int prev_nf,
+                                  int rest_nf, hipStream_t s);
+hipError_t launch_decide_after_rollback(OptDevState* st, OptHyper hp, hipStream_t s);
+hipError_t launch_clear_step(OptDevState* st, hipStream_t s);
+// theta, m, v updated in place when st->do_step; the overwritten values go to the journal (if any);
+// theta16 (if any) receives the bf16 working copy.
+hipError_t launch_adamw_step(float* theta, float* m, float* v, const float* g, float* j_theta, float* j_m,
+                             float* j_v, bf16_t* theta16, size_t n, OptHyper hp, const OptDevState* st,
+                             hipStream_t s);
+hipError_t launch_adamw_rollback(float* theta, float* m, float* v, const float* g, const float* j_theta,
+                                 const float* j_m, const float* j_v, bf16_t* theta16, size_t n, OptHyper hp,
+                                 OptDevState* st, hipStream_t s);
+
+}  // namespace zb

@@ -1,0 +1,81 @@
+"""CPU-side checks of the boundary: the C-ABI library loads, exports every symbol the header
+declares, and its host-only entry points (schedule order, stash need, configuration checks)
+agree with the oracle.  No GPU compute is called."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "zb_stage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(zb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2401_10241_amd as zb
+    names = header_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(zb.lib, n), f"{n} declared in zb_stage.h but not exported"
+    assert set(zb.binding.EXPORTED) == set(names)
+
+
+def test_schedule_order_is_bit_exact_with_oracle():
+    import paper_2401_10241_amd as zb
+    from oracle.schedule import stage_order, stash_profile
+    for kind in ("1F1B", "H1", "H2"):
+        for p in (1, 2, 3, 4, 8, 16, 32):
+            for m in (1, 2, p, 2 * p - 1, 3 * p, 64):
+                for sigma in sorted({0, p // 2, p - 1}):
+                    want = stage_order(p, sigma, m, kind)
+                    assert zb.schedule_order(p, sigma, m, kind) == want
+                    _, _, _, max_b, max_w = stash_profile(want)
+                    pb, pw, fl = zb.schedule_stash_need(p, sigma, m, kind)
+                    assert (pb, pw) == (max_b, max_w) and max(pb, pw) <= fl <= pb + pw
+
+
+def test_the_five_workload_orders():
+    import paper_2401_10241_amd as zb
+    import zb_inputs
+    from oracle.schedule import stage_order
+    for w in zb_inputs.WORKLOADS.values():
+        ops = zb.schedule_order(w.p, w.stage, w.m, w.kind)
+        assert ops == stage_order(w.p, w.stage, w.m, w.kind) and len(ops) == 3 * w.m
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    import paper_2401_10241_amd as zb
+    n = C.c_int32(0)
+    buf = (zb.binding.zb_op * 8)()
+    assert zb.lib.zb_schedule_order(4, 4, 2, 1, buf, 8, C.byref(n)) == zb.EINVAL     # stage >= p
+    assert zb.lib.zb_schedule_order(4, 0, 2, 7, buf, 8, C.byref(n)) == zb.EINVAL     # unknown kind
+    assert zb.lib.zb_schedule_order(4, 0, 4, 1, buf, 8, C.byref(n)) == zb.EINVAL     # capacity too small
+    assert n.value == 12
+    cfg = zb.binding.zb_config()
+    zb.lib.zb_config_defaults(C.byref(cfg))
+    need = C.c_size_t(0)
+    assert zb.lib.zb_stage_arena_bytes(C.byref(cfg), C.byref(need)) == zb.EINVAL     # shapes unset
+    cfg.layers, cfg.hidden, cfg.heads, cfg.ffn, cfg.seq = 3, 5120, 40, 20480, 1024
+    cfg.max_microbatches, cfg.max_pending_b, cfg.max_pending_w, cfg.max_inflight = 48, 8, 9, 16
+    assert zb.lib.zb_stage_arena_bytes(C.byref(cfg), C.byref(need)) == zb.OK
+    assert 30e9 < need.value < 120e9
+    cfg.heads = 7
+    assert zb.lib.zb_stage_arena_bytes(C.byref(cfg), C.byref(need)) == zb.EINVAL     # hidden % heads
+    h = C.c_void_p(None)
+    cfg.heads = 40
+    assert zb.lib.zb_stage_init(C.byref(cfg), C.byref(h)) == zb.EINVAL and not h.value  # no arena
+
+
+def test_stage_refuses_to_run_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    import paper_2401_10241_amd as zb
+    with pytest.raises(RuntimeError):
+        zb.Stage(layers=1, hidden=64, heads=1, ffn=256, seq=16, max_microbatches=1, max_pending_b=1,
+                 max_pending_w=1, max_inflight=1)

@@ -1,0 +1,243 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+Tolerances are the spec ones: max relative Frobenius error 1e-4 (fp32), 2e-2 (bf16);
+schedule order, rollback and accumulation determinism are bit-exact."""
+import numpy as np
+import pytest
+
+import zb_inputs
+from oracle import optimizer as O
+from oracle.schedule import stage_order
+from zb_testlib import (TOL, compare_grads, compare_outputs, load_iteration, make_device_stage, make_oracle,
+                        rel_fro)
+
+pytestmark = pytest.mark.gpu
+
+W = zb_inputs.Workload
+
+
+def run_and_compare(w, m=None, mbs_full=None):
+    import paper_2401_10241_amd as zb
+    m = m or w.m
+    params = zb_inputs.stage_params(w)
+    dev = make_device_stage(w, m)
+    orc = make_oracle(w, params)
+    dev.set_params(params)
+    dev.begin_iteration(0, m)
+    orc.begin_iteration(m)
+    load_iteration(w, 0, m, dev, orc)
+    dev.run_schedule(w.p, w.stage, m, w.kind)
+    dev.synchronize()
+    orc.run(stage_order(w.p, w.stage, m, w.kind))
+    tol = TOL[w.dtype]
+    e1 = compare_outputs(dev, orc, m, tol, mbs_full)
+    e2 = compare_grads(dev, orc, tol)
+    print(f"[{w.name}] worst rel-fro: outputs {e1:.2e}, grads {e2:.2e} (tol {tol})", flush=True)
+    dev.close()
+    return e1, e2
+
+
+def test_c1_tiny_fp32_full():
+    # BASELINE config 1: stage 0 of p=4, ZB-H1, m=8, fp32
+    run_and_compare(zb_inputs.workload("c1"))
+
+
+def test_small_bf16_mfma_shapes():
+    # bf16, shapes that are multiples of the MFMA tiles, ZB-H2 order
+    w = W("small_bf16", "bf16", 2, 256, 4, 1024, 128, 1, 4, 1, 6, "H2", seed=11)
+    run_and_compare(w)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_ragged_shapes_generic_kernels(dtype):
+    # nothing is a multiple of a tile: seq 80, hidden 72 (3 heads of 24), ffn 200, two sequences per microbatch
+    w = W("ragged", dtype, 2, 72, 3, 200, 80, 2, 3, 1, 4, "H1", seed=5)
+    run_and_compare(w)
+
+
+def test_head_dim_96_and_single_microbatch():
+    w = W("d96", "bf16", 1, 192, 2, 768, 64, 1, 2, 0, 1, "H2", seed=6)
+    run_and_compare(w)
+
+
+def test_accumulation_is_bitwise_identical_across_orders():
+    import paper_2401_10241_amd as zb
+    w = W("det", "bf16", 2, 256, 4, 1024, 128, 1, 4, 1, 8, "H1", seed=21)
+    params = zb_inputs.stage_params(w)
+    dev = make_device_stage(w, 8, pools=(8, 8, 8))
+    dev.set_params(params)
+    load_iteration(w, 0, 8, dev)
+    results = []
+    flat = [(0, k) for k in range(8)] + [(1, k) for k in range(8)] + [(2, k) for k in range(8)]
+    for order in (zb.schedule_order(4, 1, 8, "H1"), zb.schedule_order(4, 3, 8, "H2"),
+                  zb.schedule_order(8, 0, 8, "H2"), zb.schedule_order(4, 2, 8, "1F1B"), flat):
+        dev.begin_iteration(0, 8)
+        for c, k in order:
+            (dev.forward, dev.backward_input, dev.backward_weight)[c](k)
+        dev.synchronize()
+        results.append((dev.get_tensor(zb.T_FLAT_GRADS).copy(),
+                        [dev.get_tensor(zb.T_OUTPUT_DX, 0, k).copy() for k in range(8)]))
+    for g, dxs in results[1:]:
+        assert g.tobytes() == results[0][0].tobytes()
+        for a, b in zip(dxs, results[0][1]):
+            assert a.tobytes() == b.tobytes()
+    assert np.abs(results[0][0]).max() > 0
+    dev.close()
+
+
+def test_pass_order_is_enforced():
+    import paper_2401_10241_amd as zb
+    w = W("ord", "fp32", 1, 64, 2, 256, 32, 1, 2, 0, 2, "H1", seed=3)
+    dev = make_device_stage(w, 2, pools=(1, 1, 1))
+    dev.set_params(zb_inputs.stage_params(w))
+    with pytest.raises(zb.ZbError) as e:
+        dev.forward(0)
+    assert e.value.status == zb.ESTATE          # no iteration begun
+    dev.begin_iteration(0, 2)
+    load_iteration(w, 0, 2, dev)
+    for fn in (dev.backward_input, dev.backward_weight):
+        with pytest.raises(zb.ZbError) as e:
+            fn(0)
+        assert e.value.status == zb.EORDER
+    dev.forward(0)
+    with pytest.raises(zb.ZbError) as e:
+        dev.forward(0)
+    assert e.value.status == zb.EORDER
+    with pytest.raises(zb.ZbError) as e:
+        dev.forward(1)
+    assert e.value.status == zb.ENOMEM          # only one pending-B slot
+    with pytest.raises(zb.ZbError) as e:
+        dev.backward_weight(0)
+    assert e.value.status == zb.EORDER
+    dev.backward_input(0)
+    dev.backward_weight(0)
+    with pytest.raises(zb.ZbError) as e:
+        dev.forward(2)
+    assert e.value.status == zb.EINVAL
+    dev.forward(1)
+    dev.backward_input(1)
+    dev.backward_weight(1)
+    dev.synchronize()
+    dev.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# optimizer: post-validation outcomes, against the oracle's protocol and its synchronous result
+# ---------------------------------------------------------------------------------------------
+OPT_CASES = [
+    # prev_sq, rest_sq, prev_nf, rest_nf, dY scale, nan, force, outcome
+    (0.0, 0.0, False, False, 1e-3, False, False, O.COMMITTED),
+    (0.0, 4.0, False, False, 1e-3, False, False, O.ROLLED_BACK_RECLIPPED),
+    (0.0, 0.0, False, True, 1e-3, False, False, O.ROLLED_BACK_NONFINITE),
+    (0.0, float("inf"), False, False, 1e-3, False, False, O.ROLLED_BACK_NONFINITE),
+    (9.0, 0.0, False, False, 1e-3, False, False, O.DEFERRED_CLIPPED),
+    (0.0, 0.0, False, False, 1.0, False, False, O.DEFERRED_CLIPPED),
+    (9.0, 0.0, False, True, 1e-3, False, False, O.DEFERRED_SKIPPED),
+    (0.0, 0.0, True, False, 1e-3, False, False, O.SKIPPED_LOCAL),
+    (0.0, 0.0, False, False, 1e-3, True, False, O.SKIPPED_LOCAL),
+    (0.0, 0.0, False, False, 1e-3, True, True, O.ROLLED_BACK_NONFINITE),
+    (9.0, 0.0, False, False, 1e-3, False, True, O.ROLLED_BACK_RECLIPPED),
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_post_validated_optimizer_outcomes(dtype):
+    import paper_2401_10241_amd as zb
+    w = W("opt", dtype, 2, 128, 4, 512, 64, 1, 4, 1, 3, "H1", seed=31, lr=1e-3, clip=1.0)
+    m = 3
+    params = zb_inputs.stage_params(w)
+    dev = make_device_stage(w, m)
+    orc = make_oracle(w, params)
+    dev.set_params(params)
+    tol = TOL[dtype]
+    for it, (prev_sq, rest_sq, prev_nf, rest_nf, scale, nan, force, want) in enumerate(OPT_CASES):
+        dev.begin_iteration(it, m)
+        orc.begin_iteration(m)
+        for k in range(m):
+            X = zb_inputs.stage_input(w, it, k)
+            dY = zb_inputs.upstream_grad(w, it, k) * np.float32(scale)
+            if dtype == "bf16":
+                dY = zb_inputs.round_to_bf16(dY)
+            if nan and k == 1:
+                dY = dY.copy()
+                dY[5, 7] = np.nan
+            dev.set_tensor(zb.T_INPUT_X, 0, k, X)
+            dev.set_tensor(zb.T_INPUT_DY, 0, k, dY)
+            orc.set_input(k, X)
+            orc.set_upstream_grad(k, dY)
+        dev.run_schedule(w.p, w.stage, m, w.kind)
+        orc.run(stage_order(w.p, w.stage, m, w.kind))
+        before = [dev.get_tensor(x).copy() for x in (zb.T_FLAT_PARAMS, zb.T_FLAT_ADAM_M, zb.T_FLAT_ADAM_V)]
+        rep = dev.optimizer_step_validated(prev_sq, rest_sq, prev_nf, rest_nf, force)
+        ref = orc.optimizer_step(O.GlobalState(prev_sq, rest_sq, prev_nf, rest_nf, force))
+        assert rep.outcome == want == ref.outcome, (it, rep.outcome_name)
+        assert rep.t == ref.t and rep.stepped_optimistically == ref.stepped_optimistically
+        after = [dev.get_tensor(x) for x in (zb.T_FLAT_PARAMS, zb.T_FLAT_ADAM_M, zb.T_FLAT_ADAM_V)]
+        skipped = want in (O.SKIPPED_LOCAL, O.ROLLED_BACK_NONFINITE, O.DEFERRED_SKIPPED)
+        if skipped:   # bit-identical to never having stepped
+            for a, b in zip(after, before):
+                assert a.tobytes() == b.tobytes(), f"case {it}: state changed although the iteration is skipped"
+        else:
+            assert after[0].tobytes() != before[0].tobytes()
+            assert rel_fro(rep.local_sq, ref.local_sq) < (1e-6 if dtype == "fp32" else 5e-2)
+            assert rep.global_norm == pytest.approx(ref.global_norm, rel=1e-5 if dtype == "fp32" else 3e-2)
+            assert rep.clip_coef == pytest.approx(ref.clip_coef, rel=1e-5 if dtype == "fp32" else 3e-2)
+        # state against the oracle's, tensor by tensor
+        for base, ref_group in ((zb.T_PARAM, orc.master), (zb.T_ADAM_M, orc.adam_m), (zb.T_ADAM_V, orc.adam_v)):
+            got = dev.get_group(base)
+            for l in range(w.layers):
+                # Parameters that start at zero (biases, LayerNorm beta) are left out of the theta check:
+                # Adam's first update of such an element is -lr*g/(|g|+eps), i.e. lr times the SIGN of its
+                # gradient, so an element whose gradient is smaller than the bf16 rounding noise flips by
+                # 2*lr whatever the kernel does.  Their moments m and v (linear / quadratic in g) are checked.
+                names = ("wqkv", "wo", "w1", "w2", "ln1_g") if base == zb.T_PARAM else \
+                        ("wqkv", "wo", "w1", "w2", "ln1_g", "b1", "bqkv")
+                for name in names:
+                    e = rel_fro(got[l][name], ref_group[l][name])
+                    assert e <= tol, (it, base, l, name, e)
+    dev.close()
+
+
+def test_rollback_then_redo_equals_direct_clipped_step_bitwise():
+    """ROLLED_BACK_RECLIPPED must land on the same bits as DEFERRED_CLIPPED-style single clipped step."""
+    import paper_2401_10241_amd as zb
+    w = W("opt2", "bf16", 1, 128, 4, 512, 64, 1, 2, 0, 2, "H1", seed=32, lr=1e-3)
+    params = zb_inputs.stage_params(w)
+    finals = []
+    for force in (True, False):
+        dev = make_device_stage(w, 2)
+        dev.set_params(params)
+        dev.begin_iteration(0, 2)
+        load_iteration(w, 0, 2, dev)
+        dev.run_schedule(w.p, w.stage, 2, w.kind)
+        # prev_sq = 9 makes the partial norm exceed the threshold: forced -> step, rollback, redo clipped;
+        # not forced -> wait, one clipped step
+        rep = dev.optimizer_step_validated(9.0, 0.0, False, False, force)
+        assert rep.outcome == (O.ROLLED_BACK_RECLIPPED if force else O.DEFERRED_CLIPPED)
+        finals.append([dev.get_tensor(x).copy() for x in (zb.T_FLAT_PARAMS, zb.T_FLAT_ADAM_M, zb.T_FLAT_ADAM_V)])
+        if force:
+            assert rep.alg1_mismatch_elems >= 0
+        dev.close()
+    for a, b in zip(*finals):
+        assert a.tobytes() == b.tobytes()
+
+
+def test_algorithm_1_rollback_without_journal_is_close_but_not_exact():
+    import paper_2401_10241_amd as zb
+    w = W("opt3", "fp32", 1, 128, 4, 512, 64, 1, 2, 0, 2, "H1", seed=33, lr=1e-3, clip=100.0)
+    params = zb_inputs.stage_params(w)
+    dev = make_device_stage(w, 2, journal=False)
+    dev.set_params(params)
+    for it in range(2):   # the first iteration commits so that m, v are non-zero
+        dev.begin_iteration(it, 2)
+        load_iteration(w, it, 2, dev)
+        dev.run_schedule(w.p, w.stage, 2, w.kind)
+        if it == 0:
+            assert dev.optimizer_step_validated().outcome == O.COMMITTED
+    before = [dev.get_tensor(x).copy() for x in (zb.T_FLAT_PARAMS, zb.T_FLAT_ADAM_M, zb.T_FLAT_ADAM_V)]
+    rep = dev.optimizer_step_validated(0.0, 0.0, False, True, False)   # full state non-finite -> rollback
+    assert rep.outcome == O.ROLLED_BACK_NONFINITE and rep.t == 1
+    after = [dev.get_tensor(x) for x in (zb.T_FLAT_PARAMS, zb.T_FLAT_ADAM_M, zb.T_FLAT_ADAM_V)]
+    assert rel_fro(after[0], before[0]) < 1e-6
+    assert rel_fro(after[1], before[1]) < 1e-4
+    assert rel_fro(after[2], before[2]) < 1e-4
+    dev.close()

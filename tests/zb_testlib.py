@@ -1,0 +1,73 @@
+"""Helpers shared by the GPU parity tests: build a device stage (through the C ABI binding) and
+the CPU oracle from the same seeded inputs, and compare them tensor by tensor."""
+import numpy as np
+
+import zb_inputs
+from oracle import optimizer as O
+from oracle.stage import StageOracle, PARAM_ORDER
+
+TOL = {"fp32": 1e-4, "bf16": 2e-2}   # max relative Frobenius error (spec tolerances)
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a))
+
+
+def hyper(w):
+    return O.Hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.adam_eps, weight_decay=w.weight_decay, clip=w.clip)
+
+
+def make_device_stage(w, m=None, pools=None, journal=True):
+    import paper_2401_10241_amd as zb
+    m = m or w.m
+    pb, pw, fl = pools or zb.schedule_stash_need(w.p, w.stage, m, w.kind)
+    return zb.Stage(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+                    dtype=w.dtype, max_microbatches=m, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
+                    journal=journal, ln_eps=w.ln_eps, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
+                    adam_eps=w.adam_eps, weight_decay=w.weight_decay, clip=w.clip)
+
+
+def make_oracle(w, params):
+    return StageOracle(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+                       dtype=w.dtype, ln_eps=w.ln_eps, hyper=hyper(w), params=params)
+
+
+def load_iteration(w, it, m, dev=None, orc=None, mbs=None):
+    """Feeds the same seeded X_k, dY_k to the device stage and/or the oracle."""
+    import paper_2401_10241_amd as zb
+    for k in (range(m) if mbs is None else mbs):
+        X = zb_inputs.stage_input(w, it, k)
+        dY = zb_inputs.upstream_grad(w, it, k)
+        if dev is not None:
+            dev.set_tensor(zb.T_INPUT_X, 0, k, X)
+            dev.set_tensor(zb.T_INPUT_DY, 0, k, dY)
+        if orc is not None:
+            orc.set_input(k, X)
+            orc.set_upstream_grad(k, dY)
+
+
+def compare_grads(dev, orc, tol, what=None):
+    import paper_2401_10241_amd as zb
+    worst = 0.0
+    got = dev.get_group(zb.T_GRAD if what is None else what)
+    for l in range(len(got)):
+        for name in PARAM_ORDER:
+            e = rel_fro(got[l][name], orc.grads[l][name])
+            assert e <= tol, f"grad layer {l} {name}: rel fro {e:.3e} > {tol}"
+            worst = max(worst, e)
+    return worst
+
+
+def compare_outputs(dev, orc, m, tol, mbs=None):
+    import paper_2401_10241_amd as zb
+    worst = 0.0
+    for k in (range(m) if mbs is None else mbs):
+        e = rel_fro(dev.get_tensor(zb.T_OUTPUT_Y, 0, k), orc.Y[k])
+        assert e <= tol, f"Y[{k}]: rel fro {e:.3e} > {tol}"
+        e2 = rel_fro(dev.get_tensor(zb.T_OUTPUT_DX, 0, k), orc.dX[k])
+        assert e2 <= tol, f"dX[{k}]: rel fro {e2:.3e} > {tol}"
+        worst = max(worst, e, e2)
+    return worst
