@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Stage throughput of one zero-bubble pipeline stage on one MI355X.
+
+A step is one whole iteration of the hot path: gradient zeroing, all 3m passes of the workload's
+ZB-H1 / ZB-H2 order (zb_run_schedule) and, for workloads that have one, the post-validated AdamW
+step.  Inputs (parameters, all m seeded activations and upstream gradients) are resident in HBM
+before the timed region.  value = Table-1 model FLOPs (L*m*sbh(72h+12s), no causal discount) per
+second.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_FP32_TFLOPS = 157.3    # fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, seconds_hint=20.0):
+    """The oracle, as it stands, timed on the host cores on a bounded sample of the same workload:
+    one microbatch's F + B + W through ONE layer of the workload's shape."""
+    import numpy as np
+    import zb_inputs
+    from oracle.stage import StageOracle
+    from oracle.schedule import F, B, W
+    w1 = w.scaled(layers=1)
+    params = zb_inputs.stage_params(w1)
+    orc = StageOracle(layers=1, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+                      dtype=w.dtype, params=params)
+    orc.begin_iteration(1)
+    orc.set_input(0, zb_inputs.stage_input(w1, 0, 0))
+    orc.set_upstream_grad(0, zb_inputs.upstream_grad(w1, 0, 0))
+    t0 = time.perf_counter()
+    orc.run([(F, 0), (B, 0), (W, 0)])
+    dt = time.perf_counter() - t0
+    s, b, h = w.seq, w.mb_size, w.hidden
+    flops = s * b * h * (72 * h + 12 * s)
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    for var in ("OPENBLAS_NUM_THREADS", "OMP_NUM_THREADS"):
+        if os.environ.get(var, "").isdigit():
+            cores = min(cores, int(os.environ[var]))
+            break
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"numpy fp64 oracle, 1 microbatch F+B+W through 1 of the {w.layers} layers of {w.name} "
+                      f"({flops / 1e12:.2f} TFLOP of the step's {w.layers * w.m * flops / 1e12:.0f})"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--m", type=int, default=0, help="override the number of microbatches (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build covers one pipeline stage on ONE GPU; --gpus above 1 is not supported "
+              "(no collectives, no second device are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import zb_inputs
+    import paper_2401_10241_amd as zb
+
+    w = zb_inputs.workload(args.workload)
+    if args.m:
+        w = w.scaled(m=args.m)
+    m = w.m
+    torch.cuda.set_device(0)
+    pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, w.kind)
+    st = zb.Stage(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+                  dtype=w.dtype, max_microbatches=m, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
+                  lr=w.lr, beta1=w.beta1, beta2=w.beta2, adam_eps=w.adam_eps, weight_decay=w.weight_decay,
+                  clip=w.clip, ln_eps=w.ln_eps)
+    t0 = time.perf_counter()
+    st.set_params(zb_inputs.stage_params(w))
+    for k in range(m):
+        st.set_tensor(zb.T_INPUT_X, 0, k, zb_inputs.stage_input(w, 0, k))
+        st.set_tensor(zb.T_INPUT_DY, 0, k, zb_inputs.upstream_grad(w, 0, k))
+    setup_s = time.perf_counter() - t0
+
+    it_counter = [0]
+
+    def step():
+        it = it_counter[0]
+        it_counter[0] += 1
+        st.begin_iteration(it, m)
+        st.run_schedule(w.p, w.stage, m, w.kind)
+        if w.optimizer:
+            st.optimizer_step_validated(0.0, zb_inputs.rest_state(w, it), want_report=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    flops = st.model_flops(m)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    out = {
+        "metric": "stage TFLOP/s (F+B+W over m microbatches) + % bf16 MFMA peak, 1xMI355X",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "config": {"workload": f"{w.name}: stage {w.stage} of p={w.p}, ZB-{w.kind} order, m={m}, {w.layers} GPT "
+                               f"decoder layers h={w.hidden} a={w.heads} ffn={w.ffn} seq={w.seq} b={w.mb_size}"
+                               + (", validated AdamW step" if w.optimizer else ""),
+                   "model_flops_per_step": flops, "setup_seconds": round(setup_s, 1)},
+    }
+
+    if not args.no_profile:
+        # one more step with every kernel launch bracketed by HIP events on the stage's stream
+        st.profile_enable(True)
+        step()
+        stats = st.profile_read()
+        st.profile_enable(False)
+        kern = {}
+        for r in stats:
+            ms = r["total_ms"]
+            kern[r["name"]] = {"launches": r["launches"], "avg_us": round(1e3 * ms / r["launches"], 2),
+                               "total_ms": round(ms, 3),
+                               "tflops": round(r["flops"] / ms / 1e9, 1) if r["flops"] else None,
+                               "gbs": round(r["bytes"] / ms / 1e6, 1)}
+        gemm = [r for r in stats if r["name"].startswith("gemm_")]
+        g_ms = sum(r["total_ms"] for r in gemm)
+        g_fl = sum(r["flops"] for r in gemm)
+        g_n = sum(r["launches"] for r in gemm)
+        peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
+        ach = g_fl / g_ms / 1e9
+        out["roofline"] = {"kernel": "GEMM kernels (forward, dgrad, wgrad launches of one profiled step)",
+                           "bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": round(ach, 1),
+                           "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4), "traffic": None,
+                           "launches": g_n, "avg_launch_us": round(1e3 * g_ms / g_n, 2),
+                           "flops_per_launch": g_fl / g_n,
+                           "share_of_step_kernel_time": round(g_ms / sum(r["total_ms"] for r in stats), 3)}
+        out["kernels"] = kern
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

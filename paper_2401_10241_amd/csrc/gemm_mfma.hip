@@ -1,15 +1,22 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
-// One 256-thread workgroup (4 wavefronts) owns a BM x BN output tile and walks K in steps of 64.
-// Both operands are staged in LDS K-contiguous ([row][k], rows padded to 72 elements so that the
-// 16-byte fragment reads of 8 consecutive lanes fall into different banks), double buffered, with
-// the global loads of step i+1 issued before the MFMAs of step i.  An operand whose memory layout
-// has the *row* index contiguous (the weight in the forward GEMM, both operands of the wgrad GEMM)
-// is transposed on its way into LDS.
+// One 512-thread workgroup (8 wavefronts, 2 x 4) owns a BM x 256 output tile (BM = 256 or 128) and
+// walks K in steps of 64 with two LDS stages: the global loads of step i+2 are in flight and the
+// registers of step i+1 are written to LDS while the MFMAs of step i run; one barrier per step.
 //
-// MFMA operand layout (32x32x16): lane l supplies row (l & 31) of its operand and the 8 consecutive
-// k values starting at 8*(l >> 5); lane l receives column (l & 31) and rows 8*(v/4) + 4*(l>>5) + v%4
-// of the 32x32 result in accumulator element v = 0..15.
+// LDS layouts (per operand tile of R rows x 64 k):
+//   K-contiguous source ([row][k] in memory):  LDS [R][64], 128 B per row = 8 chunks of 16 B; chunk c
+//     of row r is stored at chunk position c ^ (r & 7), so both the 16-byte stores (8 lanes per row)
+//     and the 16-byte fragment reads (8 consecutive rows, same k) spread over all banks, unpadded.
+//   row-contiguous source ([k][row] in memory: the weight in the forward GEMM, both operands of the
+//     wgrad GEMM): LDS [64][R + 16] exactly as in memory, read back through the transposing LDS load
+//     ds_read_b64_tr_b16: within 16 lanes, lane a points at 4 consecutive rows (a & 3) * 4 of k-line
+//     (a >> 2) and receives, as lane r, the 4 k values of row r.  The 16-element pad makes four
+//     consecutive k-lines fall into different banks.
+//
+// MFMA 32x32x16 operand layout: lane l supplies row (l & 31) of its operand and the 8 consecutive k
+// starting at 8 * (l >> 5); it receives column (l & 31) and rows 8*(v/4) + 4*(l >> 5) + v%4 of the
+// 32 x 32 result in accumulator element v.
 #include "gemm_epilogue.h"
 
 namespace zb {
@@ -17,58 +24,89 @@ namespace zb {
 namespace {
 
 constexpr int BK = 64;
-constexpr int LDK = BK + 8;  // padded LDS row, elements
+constexpr int BN = 256;
+constexpr int NTHREADS = 512;
+constexpr int WN = 64;      // wave tile columns
+constexpr int TR_PAD = 16;  // elements
 
-template <int ROWS, bool TR>
-struct TileLoader {
-  // ROWS x 64 tile of an operand.  !TR: element (r,k) at p[r*ld + k]; TR: at p[k*ld + r].
-  static constexpr int CHUNKS = ROWS * BK / 8 / 256;  // 16-byte chunks per thread
-  uint4 reg[CHUNKS];
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-  __device__ __forceinline__ void gload(const bf16_t* __restrict__ p, long ld, int r0, int k0) {
-#pragma unroll
-    for (int j = 0; j < CHUNKS; ++j) {
-      const int c = threadIdx.x + 256 * j;
-      if (!TR) {
-        const int r = c >> 3, kc = c & 7;
-        reg[j] = *reinterpret_cast<const uint4*>(p + (long)(r0 + r) * ld + k0 + kc * 8);
-      } else {
-        const int k = c / (ROWS / 8), rc = c % (ROWS / 8);
-        reg[j] = *reinterpret_cast<const uint4*>(p + (long)(k0 + k) * ld + r0 + rc * 8);
-      }
-    }
-  }
-  __device__ __forceinline__ void lstore(bf16_t* __restrict__ s) const {
-#pragma unroll
-    for (int j = 0; j < CHUNKS; ++j) {
-      const int c = threadIdx.x + 256 * j;
-      if (!TR) {
-        const int r = c >> 3, kc = c & 7;
-        *reinterpret_cast<uint4*>(s + r * LDK + kc * 8) = reg[j];
-      } else {
-        const int k = c / (ROWS / 8), rc = c % (ROWS / 8);
-        const unsigned short* h = reinterpret_cast<const unsigned short*>(&reg[j]);
-        unsigned short* d = reinterpret_cast<unsigned short*>(s) + (rc * 8) * LDK + k;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) d[e * LDK] = h[e];
-      }
-    }
-  }
+template <int R, bool TR> struct Tile {
+  static constexpr int CHUNKS = R * BK / 8 / NTHREADS;  // 16-byte chunks per thread
+  static constexpr int PITCH = TR ? R + TR_PAD : BK;    // elements per LDS line
+  static constexpr int ELEMS = TR ? BK * PITCH : R * BK;
 };
 
-template <int BM, int BN, int WM, int WN, bool ATR, bool BTR, int MODE>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                                       int M, int N, int K, long lda, long ldb, EpiParams epi) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);      // [2][BM][LDK]
-  bf16_t* sB = sA + 2 * BM * LDK;                        // [2][BN][LDK]
-  constexpr int WAVES_N = BN / WN;
-  constexpr int MT = WM / 32, NT = WN / 32;
-  static_assert((BM / WM) * (BN / WN) == 4, "four waves per workgroup");
+// global -> registers
+template <int R, bool TR, int CH>
+__device__ __forceinline__ void gload(u32x4 (&reg)[CH], const bf16_t* __restrict__ p, long ld, int r0, int k0) {
+  static_assert(CH == Tile<R, TR>::CHUNKS, "register staging size");
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int c = threadIdx.x + NTHREADS * j;
+    if constexpr (!TR) {
+      const int r = c >> 3, kc = c & 7;
+      reg[j] = *reinterpret_cast<const u32x4*>(p + (long)(r0 + r) * ld + k0 + kc * 8);
+    } else {
+      const int k = c / (R / 8), rc = c % (R / 8);
+      reg[j] = *reinterpret_cast<const u32x4*>(p + (long)(k0 + k) * ld + r0 + rc * 8);
+    }
+  }
+}
 
-  // workgroup -> tile: consecutive workgroup ids land on different XCDs (8 of them, each with its
-  // own L2), so renumber to give each XCD a contiguous run of tiles, M fastest: the tiles that
-  // share a weight column block then sit in one L2.
+// registers -> LDS
+template <int R, bool TR, int CH>
+__device__ __forceinline__ void lstore(const u32x4 (&reg)[CH], bf16_t* __restrict__ s) {
+  static_assert(CH == Tile<R, TR>::CHUNKS, "register staging size");
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int c = threadIdx.x + NTHREADS * j;
+    if constexpr (!TR) {
+      const int r = c >> 3, kc = c & 7;
+      *reinterpret_cast<u32x4*>(s + r * BK + ((kc ^ (r & 7)) << 3)) = reg[j];
+    } else {
+      const int k = c / (R / 8), rc = c % (R / 8);
+      *reinterpret_cast<u32x4*>(s + k * Tile<R, TR>::PITCH + rc * 8) = reg[j];
+    }
+  }
+}
+
+// LDS -> one MFMA operand fragment: rows rb .. rb+31 of the tile, k = kk*16 .. kk*16+15
+template <int R, bool TR>
+__device__ __forceinline__ bf16x8 lfrag(const bf16_t* __restrict__ s, int rb, int kk, int lane) {
+  if constexpr (!TR) {
+    const int r = rb + (lane & 31);
+    const int chunk = kk * 2 + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(s + r * BK + ((chunk ^ (r & 7)) << 3));
+  } else {
+    const int blk = lane >> 4, a = lane & 15;
+    const int row = rb + ((blk & 1) << 4) + ((a & 3) << 2);
+    const int k = kk * 16 + ((blk >> 1) << 3) + (a >> 2);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const bf16_t* p0 = s + k * Tile<R, TR>::PITCH + row;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * Tile<R, TR>::PITCH));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+template <int BM, bool ATR, bool BTR, int MODE>
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
+                                                            const bf16_t* __restrict__ B, int M, int N, int K,
+                                                            long lda, long ldb, EpiParams epi) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  typedef Tile<BM, ATR> TA;
+  typedef Tile<BN, BTR> TB;
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);  // 2 stages
+  bf16_t* sB = sA + 2 * TA::ELEMS;
+  constexpr int WM = BM / 2;
+  constexpr int MT = WM / 32, NT = WN / 32;
+
+  // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that every
+  // XCD gets a contiguous run of tiles, M fastest, and tiles that share a weight block share an L2.
   const int tiles_m = M / BM;
   const int nblk = gridDim.x;
   int pid = blockIdx.x;
@@ -77,8 +115,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
   const int n0 = (pid / tiles_m) * BN;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave / WAVES_N) * WM, wn = (wave % WAVES_N) * WN;
-  const int lrow = lane & 31, lk = (lane >> 5) * 8;
+  const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -88,44 +125,46 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  TileLoader<BM, ATR> la;
-  TileLoader<BN, BTR> lb;
-  la.gload(A, lda, m0, 0);
-  lb.gload(B, ldb, n0, 0);
-  la.lstore(sA);
-  lb.lstore(sB);
+  u32x4 ra[TA::CHUNKS], rb[TB::CHUNKS];
+  gload<BM, ATR>(ra, A, lda, m0, 0);
+  gload<BN, BTR>(rb, B, ldb, n0, 0);
+  lstore<BM, ATR>(ra, sA);
+  lstore<BN, BTR>(rb, sB);
+  const int nk = K / BK;
+  if (nk > 1) {
+    gload<BM, ATR>(ra, A, lda, m0, BK);
+    gload<BN, BTR>(rb, B, ldb, n0, BK);
+  }
   __syncthreads();
 
-  int buf = 0;
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    const bool more = k0 + BK < K;
-    if (more) {
-      la.gload(A, lda, m0, k0 + BK);
-      lb.gload(B, ldb, n0, k0 + BK);
-    }
-    const bf16_t* a_s = sA + buf * BM * LDK + (wm + lrow) * LDK + lk;
-    const bf16_t* b_s = sB + buf * BN * LDK + (wn + lrow) * LDK + lk;
+  for (int it = 0; it < nk; ++it) {
+    const bf16_t* a_s = sA + (it & 1) * TA::ELEMS;
+    const bf16_t* b_s = sB + (it & 1) * TB::ELEMS;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 af[MT], bfr[NT];
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const bf16x8*>(a_s + i * 32 * LDK + kk * 16);
+      for (int i = 0; i < MT; ++i) af[i] = lfrag<BM, ATR>(a_s, wm + i * 32, kk, lane);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(b_s + j * 32 * LDK + kk * 16);
+      for (int j = 0; j < NT; ++j) bfr[j] = lfrag<BN, BTR>(b_s, wn + j * 32, kk, lane);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      la.lstore(sA + (buf ^ 1) * BM * LDK);
-      lb.lstore(sB + (buf ^ 1) * BN * LDK);
+    if (it + 1 < nk) {  // the other stage was last read in step it-1, which every wave has left
+      lstore<BM, ATR>(ra, sA + ((it + 1) & 1) * TA::ELEMS);
+      lstore<BN, BTR>(rb, sB + ((it + 1) & 1) * TB::ELEMS);
     }
     __syncthreads();
-    buf ^= 1;
+    if (it + 2 < nk) {
+      gload<BM, ATR>(ra, A, lda, m0, (it + 2) * BK);
+      gload<BN, BTR>(rb, B, ldb, n0, (it + 2) * BK);
+    }
   }
 
+  const int lrow = lane & 31, lhi = (lane >> 5) * 4;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -133,17 +172,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
       const int n = n0 + wn + j * 32 + lrow;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        const int m = m0 + wm + i * 32 + (v >> 2) * 8 + lhi + (v & 3);
         epilogue_one<bf16_t, MODE>(epi, m, n, acc[i][j][v]);
       }
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool ATR, bool BTR, int MODE>
+template <int BM, bool ATR, bool BTR, int MODE>
 hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s) {
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, ATR, BTR, MODE>;
-  constexpr size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t);
-  static bool attr_set = false;  // per instantiation; the attribute is per function, not per device state
+  auto kern = gemm_mfma_kernel<BM, ATR, BTR, MODE>;
+  constexpr size_t smem = (size_t)2 * (Tile<BM, ATR>::ELEMS + Tile<BN, BTR>::ELEMS) * sizeof(bf16_t);
+  static_assert(smem <= 160 * 1024, "LDS budget");
+  static bool attr_set = false;  // one device per process in this library
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -151,14 +191,18 @@ hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s) {
     attr_set = true;
   }
   const int grid = (g.M / BM) * (g.N / BN);
-  kern<<<grid, 256, smem, s>>>((const bf16_t*)g.A, (const bf16_t*)g.B, g.M, g.N, g.K, lda, ldb, make_epi(g));
+  kern<<<grid, NTHREADS, smem, s>>>((const bf16_t*)g.A, (const bf16_t*)g.B, g.M, g.N, g.K, lda, ldb, make_epi(g));
   return hipGetLastError();
 }
 
 template <bool ATR, bool BTR, int MODE>
 hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool* taken) {
   *taken = true;
-  if (g.M % 128 == 0 && g.N % 128 == 0) return run_cfg<128, 128, 64, 64, ATR, BTR, MODE>(g, lda, ldb, s);
+  if (g.N % BN == 0) {
+    // prefer the 256-row tile when it still gives every CU about two tiles
+    if (g.M % 256 == 0 && (long)(g.M / 256) * (g.N / BN) >= 512) return run_cfg<256, ATR, BTR, MODE>(g, lda, ldb, s);
+    if (g.M % 128 == 0) return run_cfg<128, ATR, BTR, MODE>(g, lda, ldb, s);
+  }
   *taken = false;
   return hipSuccess;
 }
