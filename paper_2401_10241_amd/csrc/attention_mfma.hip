@@ -1,7 +1,549 @@
-// MFMA attention kernels (bf16).  Shapes they do not take fall through to the generic kernels.
+// Causal multi-head attention on the gfx950 matrix cores (bf16 in, fp32 accumulate), forward and
+// backward, for head sizes 64 / 96 / 128 and sequence lengths that are multiples of 128.
+//
+// All products are formed "transposed" so that a lane owns one query (forward, dQ) or one key
+// (dK/dV) and softmax statistics never cross lanes except for one exchange between lane l and l+32:
+//   forward   S^T = K Q^T           (32 keys x 32 queries per MFMA tile; lane = query)
+//             O^T += V^T P^T        (P taken straight from the S^T accumulators as an MFMA operand)
+//   dQ pass   S^T, dP^T = V dO^T,   dS^T = P^T o (dP^T - D),   dQ^T += K^T dS^T
+//   dK/dV     S = Q K^T, dP = dO V^T (lane = key),  dV^T += dO^T P,  dK^T += Q^T dS
+// dQ and dK/dV are separate kernels (each recomputes S), so no floating-point atomics are needed and
+// results do not depend on scheduling.
+//
+// A 32x32 accumulator tile holds, in lane l and element v, row 8*(v/4) + 4*(l>>5) + v%4 and column
+// l&31.  Used directly as the k-operand of the next MFMA (16 rows per instruction: elements 0-7,
+// then 8-15), lane l's slots j = 0..7 carry rows 16*kk' + 8*(j/4) + 4*(l>>5) + j%4; the other operand
+// is fetched from LDS with the transposing load ds_read_b64_tr_b16 using the same row order.
+//
+// LDS tiles are [64 rows][D + 16] bf16 (rows = keys or queries, D contiguous); the 16-byte chunk c of
+// row r sits at chunk position c ^ ((r >> 2) & 1), which keeps both the 16-byte row reads and the
+// transposing reads free of bank conflicts.
 #include "zb_common.h"
 
 namespace zb {
+
+namespace {
+
+constexpr int QB = 128;  // rows owned by a workgroup (4 waves x 32)
+constexpr int KB = 64;   // rows of the inner-loop tile
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+template <int D> struct AT {
+  static constexpr int PITCH = D + 16;
+  static constexpr int CH = KB * D / 8 / 256;  // 16-byte chunks per thread per tile
+  static constexpr int TILE = KB * PITCH;      // elements
+};
+
+template <int D, int CH>
+__device__ __forceinline__ void gload_tile(u32x4 (&reg)[CH], const bf16_t* __restrict__ base, long ld) {
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int c = threadIdx.x + 256 * j;
+    const int row = c / (D / 8), dc = c % (D / 8);
+    reg[j] = *reinterpret_cast<const u32x4*>(base + (long)row * ld + dc * 8);
+  }
+}
+template <int D, int CH> __device__ __forceinline__ void lstore_tile(const u32x4 (&reg)[CH], bf16_t* __restrict__ s) {
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int c = threadIdx.x + 256 * j;
+    const int row = c / (D / 8), dc = c % (D / 8);
+    *reinterpret_cast<u32x4*>(s + row * AT<D>::PITCH + ((dc ^ ((row >> 2) & 1)) << 3)) = reg[j];
+  }
+}
+
+// operand fragment with rows = tile rows rb..rb+31 and k = D-columns kk*16..kk*16+15
+template <int D> __device__ __forceinline__ bf16x8 frag_rowk(const bf16_t* __restrict__ s, int rb, int kk, int lane) {
+  const int row = rb + (lane & 31);
+  const int chunk = kk * 2 + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(s + row * AT<D>::PITCH + ((chunk ^ ((row >> 2) & 1)) << 3));
+}
+
+// operand fragment with rows = D-columns eb..eb+31 and k = tile rows, in accumulator row order:
+// slots 0-3 = rows kl0 + 4*(lane>>5) + 0..3, slots 4-7 = the same + 8
+template <int D> __device__ __forceinline__ bf16x8 frag_tr(const bf16_t* __restrict__ s, int eb, int kl0, int lane) {
+  const int blk = lane >> 4, a = lane & 15;
+  const int e = eb + ((blk & 1) << 4) + ((a & 3) << 2);
+  const int kl = kl0 + ((blk >> 1) << 2) + (a >> 2);
+  const int sw = (kl >> 2) & 1;  // same for kl and kl + 8
+  const bf16_t* p = s + kl * AT<D>::PITCH + ((((e >> 3) ^ sw) << 3) | (e & 7));
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * AT<D>::PITCH));
+  return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// elements 8*half .. 8*half+7 of an accumulator tile as a bf16 k-operand
+__device__ __forceinline__ bf16x8 pack_half(const f32x16& t, int half) {
+  bf16x8 r;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r[j] = (bf16_t)t[half * 8 + j];
+  return r;
+}
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, float d) {
+  bf16x4 t;
+  t[0] = (bf16_t)a; t[1] = (bf16_t)b; t[2] = (bf16_t)c; t[3] = (bf16_t)d;
+  *reinterpret_cast<bf16x4*>(p) = t;
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+                                                       float* __restrict__ lse, int s, int a, float sl2) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
+  bf16_t* sV = sK + 2 * AT<D>::TILE;
+  const int qb = gridDim.x - 1 - blockIdx.x, head = blockIdx.y, bi = blockIdx.z;  // heaviest blocks first
+  const int h = a * D;
+  const long ld = 3L * h;
+  const long tok0 = (long)bi * s;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int hi = lane >> 5, lq = lane & 31;
+  const int qw0 = qb * QB + wave * 32;  // first query of this wave
+
+  bf16x8 qf[D / 16];
+  {
+    const bf16_t* qp = qkv + (tok0 + qw0 + lq) * ld + head * D + hi * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+  }
+  f32x16 o[D / 32];
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[et][v] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int nkb = 2 * qb + 2;
+  const bf16_t* kbase = qkv + tok0 * ld + h + head * D;
+  const bf16_t* vbase = kbase + h;
+  u32x4 rk[AT<D>::CH], rv[AT<D>::CH];
+  gload_tile<D>(rk, kbase, ld);
+  gload_tile<D>(rv, vbase, ld);
+  lstore_tile<D>(rk, sK);
+  lstore_tile<D>(rv, sV);
+  if (nkb > 1) {
+    gload_tile<D>(rk, kbase + (long)KB * ld, ld);
+    gload_tile<D>(rv, vbase + (long)KB * ld, ld);
+  }
+  __syncthreads();
+
+  for (int jb = 0; jb < nkb; ++jb) {
+    const bf16_t* kc = sK + (jb & 1) * AT<D>::TILE;
+    const bf16_t* vc = sV + (jb & 1) * AT<D>::TILE;
+    const int key0 = jb * KB;
+    if (key0 <= qw0 + 31) {  // this wave still has unmasked keys in the tile
+      const bool act1 = key0 + 32 <= qw0 + 31;
+      f32x16 st[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[t][v] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        st[0] = mfma(frag_rowk<D>(kc, 0, kk, lane), qf[kk], st[0]);
+        if (act1) st[1] = mfma(frag_rowk<D>(kc, 32, kk, lane), qf[kk], st[1]);
+      }
+      const bool diag = key0 + KB - 1 > qw0;
+      const int myq = qw0 + lq;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float x = st[t][v] * sl2;
+          if (diag) {
+            const int key = key0 + t * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
+            if (key > myq) x = -INFINITY;
+          }
+          st[t][v] = x;
+          mx = fmaxf(mx, x);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      float rs = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float p = __builtin_amdgcn_exp2f(st[t][v] - m_new);
+          st[t][v] = p;
+          rs += p;
+        }
+      rs += __shfl_xor(rs, 32, 64);
+      l = l * alpha + rs;
+      m = m_new;
+#pragma unroll
+      for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[et][v] *= alpha;
+      bf16x8 pf[4];
+      pf[0] = pack_half(st[0], 0); pf[1] = pack_half(st[0], 1);
+      pf[2] = pack_half(st[1], 0); pf[3] = pack_half(st[1], 1);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kk < 2 || act1) {
+#pragma unroll
+          for (int et = 0; et < D / 32; ++et) o[et] = mfma(frag_tr<D>(vc, et * 32, kk * 16, lane), pf[kk], o[et]);
+        }
+      }
+    }
+    if (jb + 1 < nkb) {
+      lstore_tile<D>(rk, sK + ((jb + 1) & 1) * AT<D>::TILE);
+      lstore_tile<D>(rv, sV + ((jb + 1) & 1) * AT<D>::TILE);
+    }
+    __syncthreads();
+    if (jb + 2 < nkb) {
+      gload_tile<D>(rk, kbase + (long)(jb + 2) * KB * ld, ld);
+      gload_tile<D>(rv, vbase + (long)(jb + 2) * KB * ld, ld);
+    }
+  }
+
+  const float inv = 1.0f / l;
+  bf16_t* op = out + (tok0 + qw0 + lq) * h + head * D + hi * 4;
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      store4(op + et * 32 + g * 8, o[et][4 * g] * inv, o[et][4 * g + 1] * inv, o[et][4 * g + 2] * inv,
+             o[et][4 * g + 3] * inv);
+  if (hi == 0) lse[((long)bi * a + head) * s + qw0 + lq] = (m + __builtin_amdgcn_logf(l)) * kLn2;
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, step 0: D_i = dO_i . O_i     (one wavefront per (row, head))
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void attn_bwd_prep_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
+                                                           float* __restrict__ dvec, int s, int a, int d) {
+  const int i = blockIdx.x, head = blockIdx.y, bi = blockIdx.z;
+  const long off = ((long)bi * s + i) * a * d + head * d;
+  float acc = 0.f;
+  for (int e = threadIdx.x; e < d; e += 64) acc += (float)o[off + e] * (float)dout[off + e];
+  acc = wave_sum(acc);
+  if (threadIdx.x == 0) dvec[((long)bi * a + head) * s + i] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dQ: workgroup = 128 queries, loop over key tiles up to the diagonal
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                          const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                          bf16_t* __restrict__ dqkv, int s, int a, float scale) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sV = sK + 2 * AT<D>::TILE;
+  const int qb = gridDim.x - 1 - blockIdx.x, head = blockIdx.y, bi = blockIdx.z;
+  const int h = a * D;
+  const long ld = 3L * h;
+  const long tok0 = (long)bi * s;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int hi = lane >> 5, lq = lane & 31;
+  const int qw0 = qb * QB + wave * 32;
+  const float sl2 = scale * kLog2e;
+
+  bf16x8 qf[D / 16], dof[D / 16];
+  {
+    const bf16_t* qp = qkv + (tok0 + qw0 + lq) * ld + head * D + hi * 8;
+    const bf16_t* dp = dout + (tok0 + qw0 + lq) * h + head * D + hi * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+      dof[kk] = *reinterpret_cast<const bf16x8*>(dp + kk * 16);
+    }
+  }
+  const long srow = ((long)bi * a + head) * s + qw0 + lq;
+  const float lse2 = lse[srow] * kLog2e;
+  const float Dq = dvec[srow];
+  f32x16 dq[D / 32];
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dq[et][v] = 0.f;
+
+  const int nkb = 2 * qb + 2;
+  const bf16_t* kbase = qkv + tok0 * ld + h + head * D;
+  const bf16_t* vbase = kbase + h;
+  u32x4 rk[AT<D>::CH], rv[AT<D>::CH];
+  gload_tile<D>(rk, kbase, ld);
+  gload_tile<D>(rv, vbase, ld);
+  lstore_tile<D>(rk, sK);
+  lstore_tile<D>(rv, sV);
+  if (nkb > 1) {
+    gload_tile<D>(rk, kbase + (long)KB * ld, ld);
+    gload_tile<D>(rv, vbase + (long)KB * ld, ld);
+  }
+  __syncthreads();
+
+  for (int jb = 0; jb < nkb; ++jb) {
+    const bf16_t* kc = sK + (jb & 1) * AT<D>::TILE;
+    const bf16_t* vc = sV + (jb & 1) * AT<D>::TILE;
+    const int key0 = jb * KB;
+    if (key0 <= qw0 + 31) {
+      const bool act1 = key0 + 32 <= qw0 + 31;
+      f32x16 st[2], dpt[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[t][v] = dpt[t][v] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        st[0] = mfma(frag_rowk<D>(kc, 0, kk, lane), qf[kk], st[0]);
+        dpt[0] = mfma(frag_rowk<D>(vc, 0, kk, lane), dof[kk], dpt[0]);
+        if (act1) {
+          st[1] = mfma(frag_rowk<D>(kc, 32, kk, lane), qf[kk], st[1]);
+          dpt[1] = mfma(frag_rowk<D>(vc, 32, kk, lane), dof[kk], dpt[1]);
+        }
+      }
+      const bool diag = key0 + KB - 1 > qw0;
+      const int myq = qw0 + lq;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float p = __builtin_amdgcn_exp2f(st[t][v] * sl2 - lse2);
+          if (diag) {
+            const int key = key0 + t * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
+            if (key > myq) p = 0.f;
+          }
+          st[t][v] = p * (dpt[t][v] - Dq);
+        }
+      bf16x8 dsf[4];
+      dsf[0] = pack_half(st[0], 0); dsf[1] = pack_half(st[0], 1);
+      dsf[2] = pack_half(st[1], 0); dsf[3] = pack_half(st[1], 1);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kk < 2 || act1) {
+#pragma unroll
+          for (int et = 0; et < D / 32; ++et) dq[et] = mfma(frag_tr<D>(kc, et * 32, kk * 16, lane), dsf[kk], dq[et]);
+        }
+      }
+    }
+    if (jb + 1 < nkb) {
+      lstore_tile<D>(rk, sK + ((jb + 1) & 1) * AT<D>::TILE);
+      lstore_tile<D>(rv, sV + ((jb + 1) & 1) * AT<D>::TILE);
+    }
+    __syncthreads();
+    if (jb + 2 < nkb) {
+      gload_tile<D>(rk, kbase + (long)(jb + 2) * KB * ld, ld);
+      gload_tile<D>(rv, vbase + (long)(jb + 2) * KB * ld, ld);
+    }
+  }
+  bf16_t* op = dqkv + (tok0 + qw0 + lq) * ld + head * D + hi * 4;
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      store4(op + et * 32 + g * 8, dq[et][4 * g] * scale, dq[et][4 * g + 1] * scale, dq[et][4 * g + 2] * scale,
+             dq[et][4 * g + 3] * scale);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dK and dV: workgroup = 128 keys, loop over query tiles from the diagonal to the end
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                           const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                           bf16_t* __restrict__ dqkv, int s, int a, float scale) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
+  bf16_t* sO = sQ + 2 * AT<D>::TILE;                 // dO tiles
+  float* sL = reinterpret_cast<float*>(sO + 2 * AT<D>::TILE);  // [2][64] lse * log2(e)
+  float* sD = sL + 2 * KB;                                     // [2][64] D
+  const int kb = blockIdx.x, head = blockIdx.y, bi = blockIdx.z;  // key block 0 has the most work and goes first
+  const int h = a * D;
+  const long ld = 3L * h;
+  const long tok0 = (long)bi * s;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int hi = lane >> 5, lk = lane & 31;
+  const int kw0 = kb * QB + wave * 32;  // first key of this wave
+  const float sl2 = scale * kLog2e;
+
+  bf16x8 kf[D / 16], vf[D / 16];
+  {
+    const bf16_t* kp = qkv + (tok0 + kw0 + lk) * ld + h + head * D + hi * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      kf[kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(kp + h + kk * 16);
+    }
+  }
+  f32x16 dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dk[et][v] = dv[et][v] = 0.f;
+
+  const int ib0 = kb * (QB / KB), nib = s / KB;
+  const bf16_t* qbase = qkv + tok0 * ld + head * D;
+  const bf16_t* obase = dout + tok0 * h + head * D;
+  const float* lbase = lse + ((long)bi * a + head) * s;
+  const float* dbase = dvec + ((long)bi * a + head) * s;
+  u32x4 rq[AT<D>::CH], ro[AT<D>::CH];
+  float rs = 0.f;  // threads 0..63 stage lse, 64..127 stage D
+  auto gload_stats = [&](int ib) {
+    if (threadIdx.x < KB) rs = lbase[ib * KB + threadIdx.x] * kLog2e;
+    else if (threadIdx.x < 2 * KB) rs = dbase[ib * KB + threadIdx.x - KB];
+  };
+  auto lstore_stats = [&](int stage) {
+    if (threadIdx.x < KB) sL[stage * KB + threadIdx.x] = rs;
+    else if (threadIdx.x < 2 * KB) sD[stage * KB + threadIdx.x - KB] = rs;
+  };
+  gload_tile<D>(rq, qbase + (long)ib0 * KB * ld, ld);
+  gload_tile<D>(ro, obase + (long)ib0 * KB * h, h);
+  gload_stats(ib0);
+  lstore_tile<D>(rq, sQ);
+  lstore_tile<D>(ro, sO);
+  lstore_stats(0);
+  if (ib0 + 1 < nib) {
+    gload_tile<D>(rq, qbase + (long)(ib0 + 1) * KB * ld, ld);
+    gload_tile<D>(ro, obase + (long)(ib0 + 1) * KB * h, h);
+    gload_stats(ib0 + 1);
+  }
+  __syncthreads();
+
+  for (int ib = ib0; ib < nib; ++ib) {
+    const int stage = (ib - ib0) & 1;
+    const bf16_t* qc = sQ + stage * AT<D>::TILE;
+    const bf16_t* oc = sO + stage * AT<D>::TILE;
+    const float* lc = sL + stage * KB;
+    const float* dc = sD + stage * KB;
+    const int q0 = ib * KB;
+    if (q0 + KB - 1 >= kw0) {  // some query of the tile can see this wave's keys
+      const bool act0 = q0 + 31 >= kw0;
+      f32x16 st[2], dpt[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[t][v] = dpt[t][v] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        if (act0) {
+          st[0] = mfma(frag_rowk<D>(qc, 0, kk, lane), kf[kk], st[0]);
+          dpt[0] = mfma(frag_rowk<D>(oc, 0, kk, lane), vf[kk], dpt[0]);
+        }
+        st[1] = mfma(frag_rowk<D>(qc, 32, kk, lane), kf[kk], st[1]);
+        dpt[1] = mfma(frag_rowk<D>(oc, 32, kk, lane), vf[kk], dpt[1]);
+      }
+      const bool diag = q0 < kw0 + 31;
+      const int mykey = kw0 + lk;
+      f32x16 pt[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int qi = t * 32 + g * 8 + hi * 4;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lc + qi);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dc + qi);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int v = g * 4 + i;
+            float p = __builtin_amdgcn_exp2f(st[t][v] * sl2 - l4[i]);
+            if (diag && mykey > q0 + qi + i) p = 0.f;
+            if (t == 0 && !act0) p = 0.f;
+            pt[t][v] = p;
+            st[t][v] = p * (dpt[t][v] - d4[i]);
+          }
+        }
+      bf16x8 pf[4], dsf[4];
+      pf[0] = pack_half(pt[0], 0); pf[1] = pack_half(pt[0], 1);
+      pf[2] = pack_half(pt[1], 0); pf[3] = pack_half(pt[1], 1);
+      dsf[0] = pack_half(st[0], 0); dsf[1] = pack_half(st[0], 1);
+      dsf[2] = pack_half(st[1], 0); dsf[3] = pack_half(st[1], 1);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kk >= 2 || act0) {
+#pragma unroll
+          for (int et = 0; et < D / 32; ++et) {
+            dv[et] = mfma(frag_tr<D>(oc, et * 32, kk * 16, lane), pf[kk], dv[et]);
+            dk[et] = mfma(frag_tr<D>(qc, et * 32, kk * 16, lane), dsf[kk], dk[et]);
+          }
+        }
+      }
+    }
+    if (ib + 1 < nib) {
+      lstore_tile<D>(rq, sQ + (stage ^ 1) * AT<D>::TILE);
+      lstore_tile<D>(ro, sO + (stage ^ 1) * AT<D>::TILE);
+      lstore_stats(stage ^ 1);
+    }
+    __syncthreads();
+    if (ib + 2 < nib) {
+      gload_tile<D>(rq, qbase + (long)(ib + 2) * KB * ld, ld);
+      gload_tile<D>(ro, obase + (long)(ib + 2) * KB * h, h);
+      gload_stats(ib + 2);
+    }
+  }
+  bf16_t* kp = dqkv + (tok0 + kw0 + lk) * ld + h + head * D + hi * 4;
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      store4(kp + et * 32 + g * 8, dk[et][4 * g] * scale, dk[et][4 * g + 1] * scale, dk[et][4 * g + 2] * scale,
+             dk[et][4 * g + 3] * scale);
+      store4(kp + h + et * 32 + g * 8, dv[et][4 * g], dv[et][4 * g + 1], dv[et][4 * g + 2], dv[et][4 * g + 3]);
+    }
+}
+
+template <typename K> hipError_t set_smem(K kern, size_t smem, bool* done) {
+  if (*done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)smem);
+  if (e == hipSuccess) *done = true;
+  return e;
+}
+
+template <int D> hipError_t run_fwd(const AttnArgs& a, hipStream_t s) {
+  static bool done = false;
+  constexpr size_t smem = (size_t)4 * AT<D>::TILE * sizeof(bf16_t);
+  hipError_t e = set_smem(attn_fwd_kernel<D>, smem, &done);
+  if (e != hipSuccess) return e;
+  dim3 grid(a.s / QB, a.a, a.b);
+  attn_fwd_kernel<D><<<grid, 256, smem, s>>>((const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.s, a.a,
+                                             kLog2e / sqrtf((float)D));
+  return hipGetLastError();
+}
+
+template <int D> hipError_t run_bwd(const AttnArgs& a, hipStream_t s) {
+  static bool done_q = false, done_kv = false;
+  constexpr size_t smem_q = (size_t)4 * AT<D>::TILE * sizeof(bf16_t);
+  constexpr size_t smem_kv = smem_q + 4 * KB * sizeof(float);
+  hipError_t e = set_smem(attn_bwd_dq_kernel<D>, smem_q, &done_q);
+  if (e != hipSuccess) return e;
+  e = set_smem(attn_bwd_dkv_kernel<D>, smem_kv, &done_kv);
+  if (e != hipSuccess) return e;
+  const float scale = 1.0f / sqrtf((float)D);
+  dim3 grid1(a.s, a.a, a.b);
+  attn_bwd_prep_kernel<<<grid1, 64, 0, s>>>((const bf16_t*)a.o, (const bf16_t*)a.dout, a.dvec, a.s, a.a, D);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 grid(a.s / QB, a.a, a.b);
+  attn_bwd_dq_kernel<D><<<grid, 256, smem_q, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
+                                                  (bf16_t*)a.dqkv, a.s, a.a, scale);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  attn_bwd_dkv_kernel<D><<<grid, 256, smem_kv, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
+                                                    (bf16_t*)a.dqkv, a.s, a.a, scale);
+  return hipGetLastError();
+}
+
+inline bool mfma_shape(const AttnArgs& a) {
+  return a.s % QB == 0 && (a.d == 64 || a.d == 96 || a.d == 128);
+}
+
+}  // namespace
 
 template <typename T> hipError_t launch_attention_fwd_mfma(const AttnArgs& a, hipStream_t s, bool* taken) {
   *taken = false;
@@ -11,9 +553,17 @@ template <typename T> hipError_t launch_attention_bwd_mfma(const AttnArgs& a, hi
   *taken = false;
   return hipSuccess;
 }
+template <> hipError_t launch_attention_fwd_mfma<bf16_t>(const AttnArgs& a, hipStream_t s, bool* taken) {
+  *taken = mfma_shape(a);
+  if (!*taken) return hipSuccess;
+  return a.d == 64 ? run_fwd<64>(a, s) : a.d == 96 ? run_fwd<96>(a, s) : run_fwd<128>(a, s);
+}
+template <> hipError_t launch_attention_bwd_mfma<bf16_t>(const AttnArgs& a, hipStream_t s, bool* taken) {
+  *taken = mfma_shape(a);
+  if (!*taken) return hipSuccess;
+  return a.d == 64 ? run_bwd<64>(a, s) : a.d == 96 ? run_bwd<96>(a, s) : run_bwd<128>(a, s);
+}
 template hipError_t launch_attention_fwd_mfma<float>(const AttnArgs&, hipStream_t, bool*);
-template hipError_t launch_attention_fwd_mfma<bf16_t>(const AttnArgs&, hipStream_t, bool*);
 template hipError_t launch_attention_bwd_mfma<float>(const AttnArgs&, hipStream_t, bool*);
-template hipError_t launch_attention_bwd_mfma<bf16_t>(const AttnArgs&, hipStream_t, bool*);
 
 }  // namespace zb

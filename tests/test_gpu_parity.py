@@ -59,6 +59,14 @@ def test_head_dim_96_and_single_microbatch():
     run_and_compare(w)
 
 
+@pytest.mark.parametrize("d,heads,seq,b", [(128, 2, 256, 1), (96, 2, 256, 1), (64, 4, 384, 2), (128, 1, 512, 1)])
+def test_mfma_attention_shapes(d, heads, seq, b):
+    # several query/key tiles per head, diagonal tiles, every supported head size, two sequences per microbatch
+    h = d * heads
+    w = W(f"attn_d{d}_s{seq}", "bf16", 1, h, heads, 4 * h, seq, b, 2, 0, 2, "H1", seed=40 + d)
+    run_and_compare(w)
+
+
 def test_accumulation_is_bitwise_identical_across_orders():
     import paper_2401_10241_amd as zb
     w = W("det", "bf16", 2, 256, 4, 1024, 128, 1, 4, 1, 8, "H1", seed=21)
