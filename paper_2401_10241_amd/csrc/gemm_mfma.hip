@@ -6,13 +6,14 @@
 //
 // LDS layouts (per operand tile of R rows x 64 k):
 //   K-contiguous source ([row][k] in memory):  LDS [R][64], 128 B per row = 8 chunks of 16 B; chunk c
-//     of row r is stored at chunk position c ^ (r & 7), so both the 16-byte stores (8 lanes per row)
-//     and the 16-byte fragment reads (8 consecutive rows, same k) spread over all banks, unpadded.
+//     of row r is stored at chunk position c ^ ((r >> 1) & 7).  The LDS has 64 banks of 4 bytes, so a
+//     16-byte access is served 16 lanes at a time: the stores (2 rows x 8 chunks) and the fragment
+//     reads (16 consecutive rows, same k) then each cover all 256 bytes of bank space, unpadded.
 //   row-contiguous source ([k][row] in memory: the weight in the forward GEMM, both operands of the
-//     wgrad GEMM): LDS [64][R + 16] exactly as in memory, read back through the transposing LDS load
+//     wgrad GEMM): LDS [64][R + 32] exactly as in memory, read back through the transposing LDS load
 //     ds_read_b64_tr_b16: within 16 lanes, lane a points at 4 consecutive rows (a & 3) * 4 of k-line
-//     (a >> 2) and receives, as lane r, the 4 k values of row r.  The 16-element pad makes four
-//     consecutive k-lines fall into different banks.
+//     (a >> 2) and receives, as lane r, the 4 k values of row r.  The 32-element pad puts the four
+//     k-lines that 32 lanes read together (64 bytes from each) into different quarters of the banks.
 //
 // MFMA 32x32x16 operand layout: lane l supplies row (l & 31) of its operand and the 8 consecutive k
 // starting at 8 * (l >> 5); it receives column (l & 31) and rows 8*(v/4) + 4*(l >> 5) + v%4 of the
@@ -27,7 +28,7 @@ constexpr int BK = 64;
 constexpr int BN = 256;
 constexpr int NTHREADS = 512;
 constexpr int WN = 64;      // wave tile columns
-constexpr int TR_PAD = 16;  // elements
+constexpr int TR_PAD = 32;  // elements
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -64,7 +65,7 @@ __device__ __forceinline__ void lstore(const u32x4 (&reg)[CH], bf16_t* __restric
     const int c = threadIdx.x + NTHREADS * j;
     if constexpr (!TR) {
       const int r = c >> 3, kc = c & 7;
-      *reinterpret_cast<u32x4*>(s + r * BK + ((kc ^ (r & 7)) << 3)) = reg[j];
+      *reinterpret_cast<u32x4*>(s + r * BK + ((kc ^ ((r >> 1) & 7)) << 3)) = reg[j];
     } else {
       const int k = c / (R / 8), rc = c % (R / 8);
       *reinterpret_cast<u32x4*>(s + k * Tile<R, TR>::PITCH + rc * 8) = reg[j];
@@ -78,7 +79,7 @@ __device__ __forceinline__ bf16x8 lfrag(const bf16_t* __restrict__ s, int rb, in
   if constexpr (!TR) {
     const int r = rb + (lane & 31);
     const int chunk = kk * 2 + (lane >> 5);
-    return *reinterpret_cast<const bf16x8*>(s + r * BK + ((chunk ^ (r & 7)) << 3));
+    return *reinterpret_cast<const bf16x8*>(s + r * BK + ((chunk ^ ((r >> 1) & 7)) << 3));
   } else {
     const int blk = lane >> 4, a = lane & 15;
     const int row = rb + ((blk & 1) << 4) + ((a & 3) << 2);
@@ -199,9 +200,14 @@ template <bool ATR, bool BTR, int MODE>
 hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool* taken) {
   *taken = true;
   if (g.N % BN == 0) {
-    // prefer the 256-row tile when it still gives every CU about two tiles
-    if (g.M % 256 == 0 && (long)(g.M / 256) * (g.N / BN) >= 512) return run_cfg<256, ATR, BTR, MODE>(g, lda, ldb, s);
-    if (g.M % 128 == 0) return run_cfg<128, ATR, BTR, MODE>(g, lda, ldb, s);
+    // Rounds of tiles over the 256 CUs times the tile height; the taller tile does about 1.25x the
+    // work per cycle, so it wins only when it does not cost an extra, mostly empty round.
+    const long t256 = g.M % 256 == 0 ? (long)(g.M / 256) * (g.N / BN) : 0;
+    const long t128 = g.M % 128 == 0 ? (long)(g.M / 128) * (g.N / BN) : 0;
+    const double c256 = t256 ? (double)((t256 + 255) / 256) * 256.0 / 1.25 : 1e30;
+    const double c128 = t128 ? (double)((t128 + 255) / 256) * 128.0 : 1e30;
+    if (t256 && c256 <= c128) return run_cfg<256, ATR, BTR, MODE>(g, lda, ldb, s);
+    if (t128) return run_cfg<128, ATR, BTR, MODE>(g, lda, ldb, s);
   }
   *taken = false;
   return hipSuccess;
