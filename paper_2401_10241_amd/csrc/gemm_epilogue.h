@@ -41,4 +41,41 @@ __device__ __forceinline__ void epilogue_one(const EpiParams& e, int m, int n, f
   }
 }
 
+// One 32 x 32 MFMA accumulator tile: lane holds column n and the 16 rows m0 + 8*(v/4) + (v%4), v = 0..15
+// (m0 already includes the lane's 4*(lane>>5) offset).  All reads of the tile are issued before any
+// write, so the loads overlap instead of each waiting for the previous store.
+template <typename T, int MODE>
+__device__ __forceinline__ void epilogue_tile(const EpiParams& e, int m0, int n, const f32x16& acc) {
+  size_t idx[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) idx[v] = (size_t)(m0 + (v >> 2) * 8 + (v & 3)) * e.N + n;
+  if (MODE == EPI_ACCUM_F32) {
+    float c[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) c[v] = e.outf[idx[v]];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) e.outf[idx[v]] = c[v] + acc[v];
+  } else if (MODE == EPI_BIAS_RESID || MODE == EPI_DGELU) {
+    float a[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) a[v] = to_f32(((const T*)e.aux)[idx[v]]);
+    const float b = MODE == EPI_BIAS_RESID ? e.bias[n] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      ((T*)e.out0)[idx[v]] = from_f32<T>(MODE == EPI_BIAS_RESID ? acc[v] + b + a[v] : acc[v] * gelu_grad_f(a[v]));
+  } else if (MODE == EPI_BIAS_GELU) {
+    const float b = e.bias[n];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float f = acc[v] + b;
+      ((T*)e.out0)[idx[v]] = from_f32<T>(f);
+      ((T*)e.out1)[idx[v]] = from_f32<T>(gelu_f(f));
+    }
+  } else {
+    const float b = MODE == EPI_BIAS ? e.bias[n] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) ((T*)e.out0)[idx[v]] = from_f32<T>(acc[v] + b);
+  }
+}
+
 }  // namespace zb

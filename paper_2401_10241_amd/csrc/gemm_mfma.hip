@@ -1,109 +1,139 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
-// One 512-thread workgroup (8 wavefronts, 2 x 4) owns a BM x 256 output tile (BM = 256 or 128) and
-// walks K in steps of 32 through a ring of four LDS stages.  Tiles travel global memory -> LDS
-// directly (global_load_lds_dwordx4: each lane's 16 bytes land at consecutive LDS addresses, no
-// registers in between); three tiles are in flight while the MFMAs of a fourth run.  Per step:
-// wait until this wave's loads of the current tile have landed (s_waitcnt vmcnt), one barrier
-// (all waves' loads landed, all waves done with the stage about to be refilled), issue the loads of
-// the tile three steps ahead, then fragments + MFMAs.
+//   C[M,N] (epilogue)= A * B, with B always given "row-contiguous" ([k][n] in memory, n contiguous: the
+//   weight W[in][out] in the forward GEMM, the transposed weight copy in the dgrad GEMM, dY in the wgrad
+//   GEMM) and A either K-contiguous ([m][k]: activations in forward / dgrad) or row-contiguous ([k][m]:
+//   the stashed layer input in wgrad).
 //
-// LDS layouts (no padding: the DMA writes 1 KB runs; conflicts are avoided by choosing WHICH global
+// One 512-thread workgroup (8 wavefronts, 2 x 4) owns a BM x 256 output tile (BM = 256 or 128) and walks K
+// in steps of 32.  Tiles travel global memory -> LDS directly (global_load_lds_dwordx4: each lane's 16
+// bytes land at consecutive LDS addresses, no registers in between) into rings of LDS stages, several
+// steps ahead of the MFMAs.  Per step: wait until this wave's loads of the current tiles have landed
+// (s_waitcnt vmcnt with the number of younger loads that may stay in flight), one barrier (all waves'
+// loads landed, all waves done with the stage about to be refilled), issue the loads for the step
+// BS-1 ahead, then fragments + MFMAs.
+//
+// LDS layouts (no padding: the DMA writes 1 KB runs; bank conflicts are avoided by choosing WHICH global
 // chunk each lane fetches).  The LDS has 64 banks of 4 bytes; 16-byte accesses go 16 lanes at a time,
 // 8-byte accesses 32 lanes at a time.
-//   K-contiguous source ([row][k] in memory):  LDS [R][32], 64 B per row = 4 chunks of 16 B; chunk c of
-//     row r sits at position c ^ ((r >> 2) & 3): 16 consecutive rows reading the same k cover all banks.
-//   row-contiguous source ([k][row] in memory: the weight in the forward GEMM, both operands of the
-//     wgrad GEMM): LDS [32][R]; chunk c of k-line k sits at position c ^ ((k & 3) << 2).  Read back with
-//     the transposing LDS load ds_read_b64_tr_b16: within 16 lanes, lane a points at 4 consecutive rows
-//     (a & 3) * 4 of k-line (a >> 2) and receives, as lane r, the 4 k values of row r.  32 lanes read 64 B
-//     from each of four k-lines; the swizzle puts those in different quarters of the banks.
+//   row-contiguous source: ring of BS stages of [32 k][R]; chunk c (16 B) of k-line k sits at position
+//     c ^ ((k & 3) << 2).  Read back with the transposing LDS load ds_read_b64_tr_b16: within 16 lanes,
+//     lane a points at 4 consecutive rows (a & 3) * 4 of k-line (a >> 2) and receives, as lane r, the 4 k
+//     values of row r.  32 lanes read 64 B from each of four k-lines; the swizzle puts those in
+//     different quarters of the banks.
+//   K-contiguous source: 64 k at a time (128-byte rows, so every fetched cache line is used whole), two
+//     stages of [BM][64] refilled every other step; chunk c of row r sits at position c ^ ((r >> 1) & 7):
+//     16 consecutive rows reading the same k cover all banks.
 //
 // MFMA 32x32x16 operand layout: lane l supplies row (l & 31) of its operand and the 8 consecutive k
 // starting at 8 * (l >> 5); it receives column (l & 31) and rows 8*(v/4) + 4*(l >> 5) + v%4 of the
 // 32 x 32 result in accumulator element v.
+#include <type_traits>
+
 #include "gemm_epilogue.h"
-#ifndef ZB_DIAG_DMA_COND
-#define ZB_DIAG_DMA_COND
-#endif
 #ifndef ZB_DIAG_MFMA
 #define ZB_DIAG_MFMA(x) x
+#endif
+#ifndef ZB_DIAG_EPI
+#define ZB_DIAG_EPI(x) x
 #endif
 
 namespace zb {
 
 namespace {
 
-constexpr int BK = 32;
+constexpr int KS = 32;   // k per pipeline step
 constexpr int BN = 256;
 constexpr int NTHREADS = 512;
-constexpr int WN = 64;  // wave tile columns
+constexpr int WN = 64;   // wave tile columns
+constexpr int LB = BN / 128;  // DMA instructions per wave per B tile
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
-
-template <int R> struct Tile {
-  static constexpr int ELEMS = R * BK;
-  static constexpr int WAVE_LOADS = R / 128;  // 1 KB DMA instructions per wave per tile
-};
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding)
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
-// global -> LDS, one R x 32 operand tile; s = LDS base of the tile's stage
-template <int R, bool TR>
-__device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ p, long ld, int r0, int k0, bf16_t* s, int wave,
+// global -> LDS, [32 k][R] tile of a row-contiguous operand (element (k, r) at p[k*ld + r])
+template <int R>
+__device__ __forceinline__ void dma_tr(const bf16_t* __restrict__ p, long ld, int r0, int k0, bf16_t* s, int wave,
+                                       int lane) {
+  constexpr int CPL = R / 8;  // 16-byte chunks per k-line
+#pragma unroll
+  for (int j = 0; j < R / 128; ++j) {
+    const int blk = j * 8 + wave;   // which 1 KB run of the tile
+    const int P = blk * 64 + lane;  // chunk position in LDS
+    const int k = P / CPL, c = (P % CPL) ^ ((k & 3) << 2);
+    __builtin_amdgcn_global_load_lds((gptr_t)(p + (long)(k0 + k) * ld + r0 + c * 8), (lptr_t)(s + blk * 512), 16, 0, 0);
+  }
+}
+// global -> LDS, [R][64 k] tile of a K-contiguous operand (element (r, k) at p[r*ld + k])
+template <int R>
+__device__ __forceinline__ void dma_rows(const bf16_t* __restrict__ p, long ld, int r0, int k0, bf16_t* s, int wave,
                                          int lane) {
 #pragma unroll
-  for (int j = 0; j < Tile<R>::WAVE_LOADS; ++j) {
-    const int blk = j * 8 + wave;     // which 1 KB run of the tile
-    const int P = blk * 64 + lane;    // 16-byte chunk position in LDS
-    const bf16_t* g;
-    if constexpr (!TR) {
-      const int r = P >> 2, c = (P & 3) ^ ((r >> 2) & 3);
-      g = p + (long)(r0 + r) * ld + k0 + c * 8;
-    } else {
-      constexpr int CPL = R / 8;      // chunks per k-line
-      const int k = P / CPL, c = (P % CPL) ^ ((k & 3) << 2);
-      g = p + (long)(k0 + k) * ld + r0 + c * 8;
-    }
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)(s + blk * 512), 16, 0, 0);
+  for (int j = 0; j < R / 64; ++j) {
+    const int blk = j * 8 + wave;
+    const int P = blk * 64 + lane;
+    const int r = P >> 3, c = (P & 7) ^ ((r >> 1) & 7);
+    __builtin_amdgcn_global_load_lds((gptr_t)(p + (long)(r0 + r) * ld + k0 + c * 8), (lptr_t)(s + blk * 512), 16, 0, 0);
   }
 }
 
-// LDS -> one MFMA operand fragment: rows rb .. rb+31 of the tile, k = kk*16 .. kk*16+15
-template <int R, bool TR>
-__device__ __forceinline__ bf16x8 lfrag(const bf16_t* __restrict__ s, int rb, int kk, int lane) {
-  if constexpr (!TR) {
-    const int r = rb + (lane & 31);
-    const int chunk = kk * 2 + (lane >> 5);
-    return *reinterpret_cast<const bf16x8*>(s + r * BK + ((chunk ^ ((r >> 2) & 3)) << 3));
-  } else {
-    const int blk = lane >> 4, a = lane & 15;
-    const int row = rb + ((blk & 1) << 4) + ((a & 3) << 2);
-    const int k = kk * 16 + ((blk >> 1) << 3) + (a >> 2);
-    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-    const bf16_t* p0 = s + k * R + ((((row >> 3) ^ ((k & 3) << 2)) << 3) | (row & 7));
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * R));  // k + 4: same swizzle
-    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
-  }
+// fragment of a [32][R] tile: operand rows rb..rb+31, k = kk*16 .. kk*16+15 (kk = 0, 1)
+template <int R> __device__ __forceinline__ bf16x8 frag_tr(const bf16_t* __restrict__ s, int rb, int kk, int lane) {
+  const int blk = lane >> 4, a = lane & 15;
+  const int row = rb + ((blk & 1) << 4) + ((a & 3) << 2);
+  const int k = kk * 16 + ((blk >> 1) << 3) + (a >> 2);
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const bf16_t* p0 = s + k * R + ((((row >> 3) ^ ((k & 3) << 2)) << 3) | (row & 7));
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * R));  // k + 4: same swizzle
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+// fragment of a [R][64] tile: rows rb..rb+31, k = kk*16 .. kk*16+15 (kk = 0..3)
+__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* __restrict__ s, int rb, int kk, int lane) {
+  const int r = rb + (lane & 31);
+  const int chunk = kk * 2 + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(s + r * 64 + ((chunk ^ ((r >> 1) & 7)) << 3));
 }
 
-template <int BM, int STAGES, bool ATR, bool BTR, int MODE>
-__global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
+// Number of even step indices in [it-BS+2, it-1] for a (large) step index of the given parity: the
+// steps whose A refill (K-contiguous A is refilled on even steps only) is younger than B tile `it`.
+constexpr int even_steps_in_window(int BS, int parity) {
+  int n = 0;
+  for (int i = 1000 + parity - BS + 2; i <= 1000 + parity - 1; ++i) n += (i % 2 == 0);
+  return n;
+}
+
+template <int BM, int BS, bool ATR> struct Cfg {
+  static constexpr int A_ELEMS = ATR ? KS * BM : BM * 64;      // per A stage
+  static constexpr int A_STAGES = ATR ? BS : 2;
+  static constexpr int B_ELEMS = KS * BN;
+  static constexpr int LA = ATR ? BM / 128 : BM / 64;           // DMA instructions per wave per A refill
+  static constexpr size_t SMEM = ((size_t)A_STAGES * A_ELEMS + (size_t)BS * B_ELEMS) * sizeof(bf16_t);
+  // younger loads that may still be in flight when step `it` starts computing
+  static constexpr int allowed(int parity) {
+    if (ATR) return (BS - 2) * (LA + LB);
+    const int wrt_b = (BS - 2) * LB + LA * even_steps_in_window(BS, parity);
+    if (parity) return wrt_b;               // the A tile of this pair was checked on the even step
+    return wrt_b < 2 * LB ? wrt_b : 2 * LB;  // after A(it/2): B of step it-2 and of step it-1
+  }
+};
+
+template <int BM, int BS, bool ATR, int MODE>
+__global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ B, int M, int N, int K,
                                                             long lda, long ldb, EpiParams epi) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  typedef Tile<BM> TA;
-  typedef Tile<BN> TB;
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);  // [STAGES][TA::ELEMS]
-  bf16_t* sB = sA + STAGES * TA::ELEMS;              // [STAGES][TB::ELEMS]
+  typedef Cfg<BM, BS, ATR> C;
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sB = sA + C::A_STAGES * C::A_ELEMS;
   constexpr int WM = BM / 2;
   constexpr int MT = WM / 32, NT = WN / 32;
-  constexpr int LOADS = TA::WAVE_LOADS + TB::WAVE_LOADS;  // DMA instructions per wave per k-step
 
   // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that every
   // XCD gets a contiguous run of tiles, M fastest, and tiles that share a weight block share an L2.
@@ -125,59 +155,90 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nk = K / BK;
-#pragma unroll
-  for (int t = 0; t < STAGES - 1; ++t)
-    if (t < nk) {
-      dma_tile<BM, ATR>(A, lda, m0, t * BK, sA + t * TA::ELEMS, wave, lane);
-      dma_tile<BN, BTR>(B, ldb, n0, t * BK, sB + t * TB::ELEMS, wave, lane);
-    }
+  const int nk = K / KS;  // even
 
-  for (int it = 0; it < nk; ++it) {
-    // tiles it+1 .. it+STAGES-2 may still be in flight; near the end fewer were issued, so wait for all
-    if (it + STAGES - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(LOADS * (STAGES - 2)));
+  // refills issued by step `it` (also used, with negative it, for the pipeline fill so that the order of
+  // loads is the same from the first step on)
+  auto issue = [&](int it) {
+    if constexpr (!ATR) {
+      if ((it & 1) == 0) {
+        const int j = (it >> 1) + 1;  // A tile j covers steps 2j, 2j+1 (j = -1 during the fill: nothing)
+        if (j >= 0 && 2 * j < nk) dma_rows<BM>(A, lda, m0, j * 64, sA + (j & 1) * C::A_ELEMS, wave, lane);
+      }
+    }
+    const int nt = it + BS - 1;
+    if (nt < nk) {
+      if constexpr (ATR) dma_tr<BM>(A, lda, m0, nt * KS, sA + (nt % BS) * C::A_ELEMS, wave, lane);
+      dma_tr<BN>(B, ldb, n0, nt * KS, sB + (nt % BS) * C::B_ELEMS, wave, lane);
+    }
+  };
+  // With one workgroup per CU (BS > 3) the MFMAs of the second half of every tile are issued after the
+  // NEXT step's barrier: a wave then reaches the barrier with matrix work still queued, and the matrix
+  // pipe stays busy while the waves re-synchronise and the first fragments of the new tile come out of
+  // LDS.  With two workgroups per CU the other workgroup fills those gaps and registers are scarce.
+  constexpr bool XBAR = BS > 3;
+  bf16x8 af1[MT], bf1[NT];  // fragments of the current tile's second half, kept across the barrier
+  auto load_frags = [&](int it, int parity, int kk, bf16x8 (&af)[MT], bf16x8 (&bfr)[NT]) {
+    const bf16_t* b_s = sB + (it % BS) * C::B_ELEMS;
+    const bf16_t* a_s = ATR ? sA + (it % BS) * C::A_ELEMS : sA + ((it >> 1) & 1) * C::A_ELEMS;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      if constexpr (ATR) af[i] = frag_tr<BM>(a_s, wm + i * 32, kk, lane);
+      else af[i] = frag_rows(a_s, wm + i * 32, parity * 2 + kk, lane);
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) bfr[j] = frag_tr<BN>(b_s, wn + j * 32, kk, lane);
+  };
+  auto mfmas = [&](const bf16x8 (&af)[MT], const bf16x8 (&bfr)[NT]) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        ZB_DIAG_MFMA(acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0));
+  };
+  auto step = [&](int it, auto parity_tag) {
+    constexpr int parity = decltype(parity_tag)::value;
+    // near the end fewer loads were issued than the constant assumes: wait for everything
+    if (it + BS - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::allowed(parity)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
-    const int nt = it + STAGES - 1;
-    if (nt < nk ZB_DIAG_DMA_COND) {  // refill the stage that step it-1 used
-      dma_tile<BM, ATR>(A, lda, m0, nt * BK, sA + (nt % STAGES) * TA::ELEMS, wave, lane);
-      dma_tile<BN, BTR>(B, ldb, n0, nt * BK, sB + (nt % STAGES) * TB::ELEMS, wave, lane);
+    issue(it);
+    bf16x8 af0[MT], bf0[NT];
+    load_frags(it, parity, 0, af0, bf0);
+    if constexpr (XBAR) {
+      if (it > 0) mfmas(af1, bf1);  // second half of tile it-1
+      mfmas(af0, bf0);
+      load_frags(it, parity, 1, af1, bf1);
+      // these LDS reads must have completed before the next barrier lets another wave refill the stage
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
+    } else {
+      mfmas(af0, bf0);
+      load_frags(it, parity, 1, af1, bf1);
+      mfmas(af1, bf1);
     }
-    const bf16_t* a_s = sA + (it % STAGES) * TA::ELEMS;
-    const bf16_t* b_s = sB + (it % STAGES) * TB::ELEMS;
+  };
+
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[MT], bfr[NT];
-#pragma unroll
-      for (int i = 0; i < MT; ++i) af[i] = lfrag<BM, ATR>(a_s, wm + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[j] = lfrag<BN, BTR>(b_s, wn + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-          ZB_DIAG_MFMA(acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0));
-    }
+  for (int it = 1 - BS; it < 0; ++it) issue(it);
+  for (int it = 0; it < nk; it += 2) {
+    step(it, std::integral_constant<int, 0>());
+    step(it + 1, std::integral_constant<int, 1>());
   }
+  if constexpr (XBAR) mfmas(af1, bf1);
 
   const int lrow = lane & 31, lhi = (lane >> 5) * 4;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-      const int n = n0 + wn + j * 32 + lrow;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm + i * 32 + (v >> 2) * 8 + lhi + (v & 3);
-        epilogue_one<bf16_t, MODE>(epi, m, n, acc[i][j][v]);
-      }
+      ZB_DIAG_EPI((epilogue_tile<bf16_t, MODE>(epi, m0 + wm + i * 32 + lhi, n0 + wn + j * 32 + lrow, acc[i][j])));
     }
 }
 
-template <int BM, int STAGES, bool ATR, bool BTR, int MODE>
+template <int BM, int BS, bool ATR, int MODE>
 hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s) {
-  auto kern = gemm_mfma_kernel<BM, STAGES, ATR, BTR, MODE>;
-  constexpr size_t smem = (size_t)STAGES * (Tile<BM>::ELEMS + Tile<BN>::ELEMS) * sizeof(bf16_t);
+  auto kern = gemm_mfma_kernel<BM, BS, ATR, MODE>;
+  constexpr size_t smem = Cfg<BM, BS, ATR>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool attr_set = false;  // one device per process in this library
   if (!attr_set) {
@@ -191,7 +252,7 @@ hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <bool ATR, bool BTR, int MODE>
+template <bool ATR, int MODE>
 hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool* taken) {
   *taken = true;
   if (g.N % BN == 0) {
@@ -201,12 +262,13 @@ hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool*
     const long t128 = g.M % 128 == 0 ? (long)(g.M / 128) * (g.N / BN) : 0;
     const double c256 = t256 ? (double)((t256 + 255) / 256) * 256.0 / 1.25 : 1e30;
     const double c128 = t128 ? (double)((t128 + 255) / 256) * 128.0 : 1e30;
-    if (t256 && c256 <= c128 && MODE != EPI_ACCUM_F32) return run_cfg<256, 4, ATR, BTR, MODE>(g, lda, ldb, s);
+    if (t256 && c256 <= c128 && MODE != EPI_ACCUM_F32) return run_cfg<256, ATR ? 4 : 5, ATR, MODE>(g, lda, ldb, s);
     if (t128) {
-      // more tiles than CUs: three stages (72 KB) let two workgroups share a CU, so one's epilogue and
-      // pipeline fill hide behind the other's MFMAs; otherwise one workgroup per CU with a deeper ring
-      if (t128 > 256) return run_cfg<128, 3, ATR, BTR, MODE>(g, lda, ldb, s);
-      return run_cfg<128, 4, ATR, BTR, MODE>(g, lda, ldb, s);
+      // more tiles than CUs: a three-stage ring (<= 80 KB) lets two workgroups share a CU, so one's
+      // epilogue and pipeline fill hide behind the other's MFMAs; otherwise one workgroup per CU with a
+      // deeper ring
+      if (t128 > 256) return run_cfg<128, 3, ATR, MODE>(g, lda, ldb, s);
+      return run_cfg<128, 5, ATR, MODE>(g, lda, ldb, s);
     }
   }
   *taken = false;
@@ -225,17 +287,17 @@ template <typename T> hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t
 template <> hipError_t launch_gemm_mfma<bf16_t>(const GemmArgs& g, hipStream_t s, bool* taken) {
   *taken = false;
   const bool atr = g.a_sm == 1 && g.a_sk != 1, btr = g.b_sn == 1 && g.b_sk != 1;
-  const long lda = atr ? g.a_sk : g.a_sm, ldb = btr ? g.b_sk : g.b_sn;
-  if (g.K % BK != 0 || lda % 8 != 0 || ldb % 8 != 0 || !aligned16(g.A) || !aligned16(g.B)) return hipSuccess;
-  if (!atr && btr) {  // forward: X[M,K] * W[K,N]
-    if (g.epilogue == EPI_BIAS) return run_shape<false, true, EPI_BIAS>(g, lda, ldb, s, taken);
-    if (g.epilogue == EPI_BIAS_RESID) return run_shape<false, true, EPI_BIAS_RESID>(g, lda, ldb, s, taken);
-    if (g.epilogue == EPI_BIAS_GELU) return run_shape<false, true, EPI_BIAS_GELU>(g, lda, ldb, s, taken);
-  } else if (!atr && !btr) {  // dgrad: dY[M,K'] * W[N,K']^T
-    if (g.epilogue == EPI_STORE) return run_shape<false, false, EPI_STORE>(g, lda, ldb, s, taken);
-    if (g.epilogue == EPI_DGELU) return run_shape<false, false, EPI_DGELU>(g, lda, ldb, s, taken);
-  } else if (atr && btr) {  // wgrad: X[K,M]^T * dY[K,N]
-    if (g.epilogue == EPI_ACCUM_F32) return run_shape<true, true, EPI_ACCUM_F32>(g, lda, ldb, s, taken);
+  if (!btr) return hipSuccess;  // B must be row-contiguous
+  const long lda = atr ? g.a_sk : g.a_sm, ldb = g.b_sk;
+  if (g.K % 64 != 0 || lda % 8 != 0 || ldb % 8 != 0 || !aligned16(g.A) || !aligned16(g.B)) return hipSuccess;
+  if (!atr) {  // forward X[M,K] * W[K,N]; dgrad dY[M,K'] * Wt[K',N']
+    if (g.epilogue == EPI_BIAS) return run_shape<false, EPI_BIAS>(g, lda, ldb, s, taken);
+    if (g.epilogue == EPI_BIAS_RESID) return run_shape<false, EPI_BIAS_RESID>(g, lda, ldb, s, taken);
+    if (g.epilogue == EPI_BIAS_GELU) return run_shape<false, EPI_BIAS_GELU>(g, lda, ldb, s, taken);
+    if (g.epilogue == EPI_STORE) return run_shape<false, EPI_STORE>(g, lda, ldb, s, taken);
+    if (g.epilogue == EPI_DGELU) return run_shape<false, EPI_DGELU>(g, lda, ldb, s, taken);
+  } else {  // wgrad: X[K,M]^T * dY[K,N]
+    if (g.epilogue == EPI_ACCUM_F32) return run_shape<true, EPI_ACCUM_F32>(g, lda, ldb, s, taken);
   }
   return hipSuccess;
 }

@@ -212,6 +212,23 @@ __global__ __launch_bounds__(kThreads) void colsum_accum_kernel(const T* __restr
   }
 }
 
+// dst[c][r] = src[r][c] for a [rows][cols] bf16 matrix; 64 x 64 tiles through LDS
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const unsigned short* __restrict__ src,
+                                                             unsigned short* __restrict__ dst, int rows, int cols) {
+  __shared__ unsigned short tile[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    tile[i][tx] = (r < rows && c < cols) ? src[(size_t)r * cols + c] : (unsigned short)0;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (c < cols && r < rows) dst[(size_t)c * rows + r] = tile[tx][i];
+  }
+}
+
 __global__ void fill_f32_kernel(float* p, size_t n, float v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -264,6 +281,13 @@ template <typename T> hipError_t launch_colsum_accum(const T* dy, float* db, int
   if (n % kV != 0 || rows <= 0) return hipErrorInvalidValue;
   const int per_block = 16 * kV;
   colsum_accum_kernel<T, kV><<<(n + per_block - 1) / per_block, kThreads, 0, s>>>(dy, db, rows, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_bf16(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipErrorInvalidValue;
+  dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+  transpose_bf16_kernel<<<grid, 256, 0, s>>>((const unsigned short*)src, (unsigned short*)dst, rows, cols);
   return hipGetLastError();
 }
 

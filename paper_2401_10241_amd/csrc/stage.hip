@@ -40,11 +40,11 @@ struct LayerOff {  // byte offsets inside one slot of each pool
 
 enum KClass {
   KC_GEMM_FWD = 0, KC_GEMM_DGRAD, KC_GEMM_WGRAD, KC_ATTN_FWD, KC_ATTN_BWD, KC_LN_FWD, KC_LN_BWD, KC_COLSUM,
-  KC_FILL, KC_SUMSQ, KC_ADAMW_STEP, KC_ADAMW_ROLLBACK, KC_COUNT
+  KC_FILL, KC_SUMSQ, KC_ADAMW_STEP, KC_ADAMW_ROLLBACK, KC_TRANSPOSE, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd", "layernorm_bwd",
-    "bias_grad_colsum", "grad_zero_fill", "grad_sumsq", "adamw_step", "adamw_rollback"};
+    "bias_grad_colsum", "grad_zero_fill", "grad_sumsq", "adamw_step", "adamw_rollback", "weight_transpose"};
 
 struct ProfRec {
   int cls;
@@ -67,6 +67,7 @@ struct zb_stage {
   float *theta = nullptr, *grad = nullptr, *adam_m = nullptr, *adam_v = nullptr;
   float *j_theta = nullptr, *j_m = nullptr, *j_v = nullptr;
   bf16_t* theta16 = nullptr;
+  bf16_t* theta16_t = nullptr;  // the four weight matrices transposed ([out][in]), for the dgrad GEMMs
 
   char *in_x = nullptr, *in_dy = nullptr, *out_y = nullptr, *out_dx = nullptr;
   size_t act_bytes = 0;  // one [T, h] tensor
@@ -97,6 +98,7 @@ struct zb_stage {
   const void* Wt(int l, int i) const {
     return bf16 ? (const void*)(theta16 + poff[l * ZB_P_COUNT + i]) : (const void*)P(l, i);
   }
+  const void* WtT(int l, int i) const { return theta16_t + poff[l * ZB_P_COUNT + i]; }
 };
 
 namespace {
@@ -186,7 +188,10 @@ size_t layout(zb_stage* st, void* arena) {
     st->j_m = bp.take<float>(fb);
     st->j_v = bp.take<float>(fb);
   }
-  if (st->bf16) st->theta16 = bp.take<bf16_t>(o * sizeof(bf16_t));
+  if (st->bf16) {
+    st->theta16 = bp.take<bf16_t>(o * sizeof(bf16_t));
+    st->theta16_t = bp.take<bf16_t>(o * sizeof(bf16_t));
+  }
 
   const size_t E = st->esz;
   st->act_bytes = align_up(T * h * E);
@@ -268,7 +273,37 @@ void build_order(int p, int sigma, int m, int kind, std::vector<zb_op>* out) {
   for (int k = m - delta; k < m; ++k) out->push_back({ZB_PASS_W, k});
 }
 
+// rows (= in features) and columns of weight matrix i
+void weight_dims(const zb_stage* st, int i, int* rows, int* cols) {
+  const int h = st->h, f = st->ffn;
+  *rows = i == ZB_P_W2 ? f : h;
+  *cols = i == ZB_P_WQKV ? 3 * h : i == ZB_P_W1 ? f : h;
+}
+const int kMatrices[4] = {ZB_P_WQKV, ZB_P_WO, ZB_P_W1, ZB_P_W2};
+
+// refresh the transposed bf16 copy of one weight matrix (bf16 stages only)
+hipError_t refresh_transposed(zb_stage* st, int l, int i) {
+  if (!st->bf16) return hipSuccess;
+  int rows, cols;
+  weight_dims(st, i, &rows, &cols);
+  const size_t off = st->poff[l * ZB_P_COUNT + i];
+  return launch_transpose_bf16(st->theta16 + off, st->theta16_t + off, rows, cols, st->stream);
+}
+
 template <typename T> struct Exec {
+  // B operand of a dgrad GEMM dIn[T, n_in] = dOut[T, k_out] * W^T with W = [n_in][k_out]
+  static void dgrad_weight(zb_stage* st, GemmArgs* g, int l, int wi, int n_in, int k_out) {
+    if (st->bf16) {  // transposed copy [k_out][n_in]: row-contiguous, as the MFMA kernel wants it
+      g->B = st->WtT(l, wi);
+      g->b_sk = n_in;
+      g->b_sn = 1;
+    } else {
+      g->B = st->Wt(l, wi);
+      g->b_sk = 1;
+      g->b_sn = k_out;
+    }
+  }
+
   static hipError_t gemm(zb_stage* st, int cls, const GemmArgs& g) {
     double bytes = 0;
     const double E = sizeof(T);
@@ -364,13 +399,13 @@ template <typename T> struct Exec {
       T* dx = l == 0 ? (T*)(st->out_dx + st->act_bytes * (size_t)mb) : (T*)(bw + st->lo[l - 1].bw_dy);
 
       GemmArgs g{};  // dFh = (dY W2^T) * gelu'(Fh)
-      g.A = dy; g.B = st->Wt(l, ZB_P_W2); g.M = T_; g.N = f; g.K = h;
-      g.a_sm = h; g.a_sk = 1; g.b_sk = 1; g.b_sn = h;
+      g.A = dy; g.M = T_; g.N = f; g.K = h;
+      g.a_sm = h; g.a_sk = 1; dgrad_weight(st, &g, l, ZB_P_W2, f, h);
       g.epilogue = EPI_DGELU; g.out0 = dFh; g.aux = Fh;
       ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
       g = GemmArgs{};  // dU = dFh W1^T
-      g.A = dFh; g.B = st->Wt(l, ZB_P_W1); g.M = T_; g.N = h; g.K = f;
-      g.a_sm = f; g.a_sk = 1; g.b_sk = 1; g.b_sn = f;
+      g.A = dFh; g.M = T_; g.N = h; g.K = f;
+      g.a_sm = f; g.a_sk = 1; dgrad_weight(st, &g, l, ZB_P_W1, h, f);
       g.epilogue = EPI_STORE; g.out0 = tmp;
       ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
       {
@@ -379,8 +414,8 @@ template <typename T> struct Exec {
                                             st->G(l, ZB_P_LN2_B), st->ln_partials, T_, h, s));
       }
       g = GemmArgs{};  // dC = dY1 Wo^T
-      g.A = dY1; g.B = st->Wt(l, ZB_P_WO); g.M = T_; g.N = h; g.K = h;
-      g.a_sm = h; g.a_sk = 1; g.b_sk = 1; g.b_sn = h;
+      g.A = dY1; g.M = T_; g.N = h; g.K = h;
+      g.a_sm = h; g.a_sk = 1; dgrad_weight(st, &g, l, ZB_P_WO, h, h);
       g.epilogue = EPI_STORE; g.out0 = tmp;
       ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
       {
@@ -391,8 +426,8 @@ template <typename T> struct Exec {
         ZB_HIP(st, launch_attention_bwd<T>(aa, s));
       }
       g = GemmArgs{};  // dA = dQKV Wqkv^T
-      g.A = dQKV; g.B = st->Wt(l, ZB_P_WQKV); g.M = T_; g.N = h; g.K = 3 * h;
-      g.a_sm = 3 * h; g.a_sk = 1; g.b_sk = 1; g.b_sn = 3 * h;
+      g.A = dQKV; g.M = T_; g.N = h; g.K = 3 * h;
+      g.a_sm = 3 * h; g.a_sk = 1; dgrad_weight(st, &g, l, ZB_P_WQKV, h, 3 * h);
       g.epilogue = EPI_STORE; g.out0 = tmp;
       ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
       {
@@ -705,6 +740,11 @@ zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, z
                                  st->theta16, n, st->hp, st->opt, s));
   }
   ZB_HIP(st, launch_clear_step(st->opt, s));
+  if (st->bf16) {  // the dgrad GEMMs read the weights transposed
+    ProfScope ps(st, KC_TRANSPOSE, 0, 4.0 * 12.0 * st->h * (double)st->h * st->L);
+    for (int l = 0; l < st->L; ++l)
+      for (int wi : kMatrices) ZB_HIP(st, refresh_transposed(st, l, wi));
+  }
   if (report) {
     OptDevState h;
     ZB_HIP(st, hipMemcpyAsync(&h, st->opt, sizeof(h), hipMemcpyDeviceToHost, s));
@@ -754,8 +794,11 @@ zb_status zb_set_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, c
     ZB_HIP(st, launch_convert_from_f32<bf16_t>(st->staging, (bf16_t*)r.ptr, r.count, s));
   } else {
     ZB_HIP(st, hipMemcpyAsync(r.ptr, host_src, bytes, hipMemcpyHostToDevice, s));
-    if (r.is_param && st->bf16)
+    if (r.is_param && st->bf16) {
       ZB_HIP(st, launch_convert_from_f32<bf16_t>((const float*)r.ptr, st->theta16 + r.flat_off, r.count, s));
+      const int pi = what % 16;
+      if (pi == ZB_P_WQKV || pi == ZB_P_WO || pi == ZB_P_W1 || pi == ZB_P_W2) ZB_HIP(st, refresh_transposed(st, layer, pi));
+    }
   }
   ZB_HIP(st, hipStreamSynchronize(s));
   return ZB_OK;

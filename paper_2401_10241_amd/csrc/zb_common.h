@@ -110,6 +110,7 @@ template <typename T>
 hipError_t launch_colsum_accum(const T* dy, float* db, int rows, int n, hipStream_t s);
 
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
+hipError_t launch_transpose_bf16(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t s);
 template <typename T> hipError_t launch_convert_from_f32(const float* src, T* dst, size_t n, hipStream_t s);
 template <typename T> hipError_t launch_convert_to_f32(const T* src, float* dst, size_t n, hipStream_t s);
 template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStream_t s);
