@@ -97,64 +97,89 @@ __global__ __launch_bounds__(kThreads) void layernorm_fwd_kernel(const T* __rest
   }
 }
 
+// sums of two values over the 256 threads of a workgroup with one exchange
+__device__ __forceinline__ void block_sum2(float& a, float& b, float (*red)[2]) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  __syncthreads();
+  if (lane == 0) { red[wave][0] = a; red[wave][1] = b; }
+  __syncthreads();
+  a = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
+  b = (red[0][1] + red[1][1]) + (red[2][1] + red[3][1]);
+}
+
 // Each workgroup walks rows blockIdx.x, blockIdx.x + gridDim.x, ... and keeps per-column partial
-// sums of g*xhat and g in registers; they are written to partials[block][0/1][h].
-template <typename T>
+// sums of g*xhat and g in registers; they are written to partials[block][0/1][h].  The next row's
+// operands are fetched while the current row is reduced.  NCH = ceil(h / 1024) chunks of 4 per lane.
+template <typename T, int NCH>
 __global__ __launch_bounds__(kThreads) void layernorm_bwd_kernel(const T* __restrict__ g, const T* __restrict__ x,
                                                                  const float* __restrict__ stats,
                                                                  const float* __restrict__ gamma,
                                                                  const T* __restrict__ resid, T* __restrict__ dx,
                                                                  float* __restrict__ partials, int rows, int h) {
-  __shared__ float red[4];
-  float gam[kMaxChunks][kVec];
-  float pg[kMaxChunks][kVec], pb[kMaxChunks][kVec];
+  __shared__ float red[4][2];
+  float gam[NCH][kVec], pg[NCH][kVec], pb[NCH][kVec];
 #pragma unroll
-  for (int c = 0; c < kMaxChunks; ++c) {
+  for (int c = 0; c < NCH; ++c) {
     const int col = (c * kThreads + threadIdx.x) * kVec;
     if (col < h) Vec4<float>::load(gamma + col, gam[c]);
 #pragma unroll
     for (int e = 0; e < kVec; ++e) pg[c][e] = pb[c][e] = 0.f;
   }
-  for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+  float gv[NCH][kVec], xv[NCH][kVec], rv[NCH][kVec];
+  auto fetch = [&](int row) {
     const size_t off = (size_t)row * h;
-    const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
-    float gg[kMaxChunks][kVec], xh[kMaxChunks][kVec];
-    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int c = 0; c < kMaxChunks; ++c) {
+    for (int c = 0; c < NCH; ++c) {
       const int col = (c * kThreads + threadIdx.x) * kVec;
       if (col < h) {
-        float gv[4], xv[4];
-        Vec4<T>::load(g + off + col, gv);
-        Vec4<T>::load(x + off + col, xv);
+        Vec4<T>::load(g + off + col, gv[c]);
+        Vec4<T>::load(x + off + col, xv[c]);
+        Vec4<T>::load(resid + off + col, rv[c]);
+      }
+    }
+  };
+  int row = blockIdx.x;
+  if (row < rows) fetch(row);
+  for (; row < rows; row += gridDim.x) {
+    const size_t off = (size_t)row * h;
+    const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+    float gg[NCH][kVec], xh[NCH][kVec], rr[NCH][kVec];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (c * kThreads + threadIdx.x) * kVec;
+      if (col < h) {
 #pragma unroll
         for (int e = 0; e < kVec; ++e) {
-          xh[c][e] = (xv[e] - mean) * rstd;
-          pg[c][e] += gv[e] * xh[c][e];
-          pb[c][e] += gv[e];
-          gg[c][e] = gv[e] * gam[c][e];
+          xh[c][e] = (xv[c][e] - mean) * rstd;
+          pg[c][e] += gv[c][e] * xh[c][e];
+          pb[c][e] += gv[c][e];
+          gg[c][e] = gv[c][e] * gam[c][e];
+          rr[c][e] = rv[c][e];
           s1 += gg[c][e];
           s2 += gg[c][e] * xh[c][e];
         }
       }
     }
-    const float m1 = block_sum(s1, red) / (float)h;
-    const float m2 = block_sum(s2, red) / (float)h;
+    if (row + (int)gridDim.x < rows) fetch(row + gridDim.x);
+    block_sum2(s1, s2, red);
+    const float m1 = s1 / (float)h, m2 = s2 / (float)h;
 #pragma unroll
-    for (int c = 0; c < kMaxChunks; ++c) {
+    for (int c = 0; c < NCH; ++c) {
       const int col = (c * kThreads + threadIdx.x) * kVec;
       if (col < h) {
-        float rv[4], o[4];
-        Vec4<T>::load(resid + off + col, rv);
+        float o[4];
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) o[e] = rv[e] + rstd * (gg[c][e] - m1 - xh[c][e] * m2);
+        for (int e = 0; e < kVec; ++e) o[e] = rr[c][e] + rstd * (gg[c][e] - m1 - xh[c][e] * m2);
         Vec4<T>::store(dx + off + col, o);
       }
     }
   }
   float* p0 = partials + (size_t)blockIdx.x * 2 * h;
 #pragma unroll
-  for (int c = 0; c < kMaxChunks; ++c) {
+  for (int c = 0; c < NCH; ++c) {
     const int col = (c * kThreads + threadIdx.x) * kVec;
     if (col < h) {
       Vec4<float>::store(p0 + col, pg[c]);
@@ -163,32 +188,48 @@ __global__ __launch_bounds__(kThreads) void layernorm_bwd_kernel(const T* __rest
   }
 }
 
-// dgamma[c] += sum_b partials[b][0][c]; dbeta[c] += sum_b partials[b][1][c]   (fixed order)
-__global__ void layernorm_bwd_reduce_kernel(const float* __restrict__ partials, float* __restrict__ dgamma,
-                                            float* __restrict__ dbeta, int blocks, int h) {
-  const int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= h) return;
+// dgamma[c] += sum_b partials[b][0][c]; dbeta[c] += sum_b partials[b][1][c], always in the same order:
+// 64 columns per workgroup, four groups of lanes each add a quarter of the blocks in order, then the
+// four group sums are added in order.
+__global__ __launch_bounds__(256) void layernorm_bwd_reduce_kernel(const float* __restrict__ partials,
+                                                                   float* __restrict__ dgamma,
+                                                                   float* __restrict__ dbeta, int blocks, int h) {
+  __shared__ float red[4][2][64];
+  const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cl;
   float a = 0.f, b = 0.f;
-  for (int k = 0; k < blocks; ++k) {
-    a += partials[(size_t)k * 2 * h + col];
-    b += partials[(size_t)k * 2 * h + h + col];
+  if (col < h) {
+    const int per = (blocks + 3) / 4;
+    const int k1 = min(blocks, (grp + 1) * per);
+    for (int k = grp * per; k < k1; ++k) {
+      a += partials[(size_t)k * 2 * h + col];
+      b += partials[(size_t)k * 2 * h + h + col];
+    }
   }
-  dgamma[col] += a;
-  dbeta[col] += b;
+  red[grp][0][cl] = a;
+  red[grp][1][cl] = b;
+  __syncthreads();
+  if (grp == 0 && col < h) {
+    dgamma[col] += (red[0][0][cl] + red[1][0][cl]) + (red[2][0][cl] + red[3][0][cl]);
+    dbeta[col] += (red[0][1][cl] + red[1][1][cl]) + (red[2][1][cl] + red[3][1][cl]);
+  }
 }
 
-// 256 threads = 16 column-lanes (each kV consecutive columns) x 16 row groups
+// Bias gradient, stage 1: column sums of one slice of rows.  256 threads = 16 column-lanes (each kV
+// consecutive columns) x 16 row groups; grid.y = row slices; out[slice][n].
 template <typename T, int kV>
-__global__ __launch_bounds__(kThreads) void colsum_accum_kernel(const T* __restrict__ dy, float* __restrict__ db,
-                                                                int rows, int n) {
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __restrict__ dy, float* __restrict__ out,
+                                                                  int rows, int n, int rows_per_slice) {
   __shared__ float red[16][16 * kV + 1];
   const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
   const int col = (blockIdx.x * 16 + cl) * kV;
+  const int r_begin = blockIdx.y * rows_per_slice;
+  const int r_end = min(rows, r_begin + rows_per_slice);
   float acc[kV];
 #pragma unroll
   for (int e = 0; e < kV; ++e) acc[e] = 0.f;
   if (col < n) {
-    for (int r = rg; r < rows; r += 16) {
+    for (int r = r_begin + rg; r < r_end; r += 16) {
       const T* p = dy + (size_t)r * n + col;
 #pragma unroll
       for (int e = 0; e < kV; e += 4) {
@@ -207,9 +248,17 @@ __global__ __launch_bounds__(kThreads) void colsum_accum_kernel(const T* __restr
       float t = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) t += red[r][threadIdx.x];
-      db[c] += t;
+      out[(size_t)blockIdx.y * n + c] = t;
     }
   }
+}
+// stage 2: db[c] += slices added in order
+__global__ void colsum_final_kernel(const float* __restrict__ part, float* __restrict__ db, int slices, int n) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  float t = 0.f;
+  for (int k = 0; k < slices; ++k) t += part[(size_t)k * n + c];
+  db[c] += t;
 }
 
 // dst[c][r] = src[r][c] for a [rows][cols] bf16 matrix; 64 x 64 tiles through LDS
@@ -263,24 +312,46 @@ hipError_t launch_layernorm_fwd(const T* x, const float* gamma, const float* bet
   return hipGetLastError();
 }
 
+template <typename T, int NCH>
+hipError_t run_ln_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid, T* dx,
+                      float* partials, int rows, int h, int blocks, hipStream_t s) {
+  layernorm_bwd_kernel<T, NCH><<<blocks, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, partials, rows, h);
+  return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid,
                                 T* dx, float* dgamma, float* dbeta, float* partials, int rows, int h,
                                 hipStream_t s) {
   if (h % kVec != 0 || h > kThreads * kVec * kMaxChunks || rows <= 0) return hipErrorInvalidValue;
   const int blocks = rows < kLnBwdBlocks ? rows : kLnBwdBlocks;
-  layernorm_bwd_kernel<T><<<blocks, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, partials, rows, h);
-  hipError_t e = hipGetLastError();
+  const int nch = (h + kThreads * kVec - 1) / (kThreads * kVec);
+  hipError_t e;
+  switch (nch) {
+    case 1: e = run_ln_bwd<T, 1>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+    case 2: e = run_ln_bwd<T, 2>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+    case 3: e = run_ln_bwd<T, 3>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+    case 4: e = run_ln_bwd<T, 4>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+    case 5: e = run_ln_bwd<T, 5>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+    case 6: e = run_ln_bwd<T, 6>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+    default: e = run_ln_bwd<T, 8>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+  }
   if (e != hipSuccess) return e;
-  layernorm_bwd_reduce_kernel<<<(h + 255) / 256, 256, 0, s>>>(partials, dgamma, dbeta, blocks, h);
+  layernorm_bwd_reduce_kernel<<<(h + 63) / 64, 256, 0, s>>>(partials, dgamma, dbeta, blocks, h);
   return hipGetLastError();
 }
 
-template <typename T> hipError_t launch_colsum_accum(const T* dy, float* db, int rows, int n, hipStream_t s) {
+template <typename T>
+hipError_t launch_colsum_accum(const T* dy, float* db, float* scratch, int rows, int n, hipStream_t s) {
   constexpr int kV = 16 / sizeof(T);
   if (n % kV != 0 || rows <= 0) return hipErrorInvalidValue;
+  const int slices = rows >= 8 * 16 ? kColsumSlices : 1;
   const int per_block = 16 * kV;
-  colsum_accum_kernel<T, kV><<<(n + per_block - 1) / per_block, kThreads, 0, s>>>(dy, db, rows, n);
+  dim3 grid((n + per_block - 1) / per_block, slices);
+  colsum_partial_kernel<T, kV><<<grid, kThreads, 0, s>>>(dy, scratch, rows, n, (rows + slices - 1) / slices);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  colsum_final_kernel<<<(n + 255) / 256, 256, 0, s>>>(scratch, db, slices, n);
   return hipGetLastError();
 }
 
@@ -316,7 +387,7 @@ template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStr
                                               hipStream_t);                                                      \
   template hipError_t launch_layernorm_bwd<T>(const T*, const T*, const float*, const float*, const T*, T*,      \
                                               float*, float*, float*, int, int, hipStream_t);                    \
-  template hipError_t launch_colsum_accum<T>(const T*, float*, int, int, hipStream_t);                           \
+  template hipError_t launch_colsum_accum<T>(const T*, float*, float*, int, int, hipStream_t);                           \
   template hipError_t launch_convert_from_f32<T>(const float*, T*, size_t, hipStream_t);                         \
   template hipError_t launch_convert_to_f32<T>(const T*, float*, size_t, hipStream_t);                           \
   template hipError_t launch_poke<T>(T*, size_t, float, hipStream_t);

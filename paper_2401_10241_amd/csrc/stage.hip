@@ -229,7 +229,12 @@ size_t layout(zb_stage* st, void* arena) {
 
   st->tmp = bp.take<char>(T * h * E);
   st->dvec = bp.take<float>((size_t)st->b * st->a * st->s * sizeof(float));
-  st->ln_partials = bp.take<float>((size_t)kLnBwdBlocks * 2 * h * sizeof(float));
+  {  // LayerNorm-backward partials; the bias-gradient column sums reuse it for their row slices
+    size_t need = (size_t)kLnBwdBlocks * 2 * h;
+    const size_t widest = f > 3 * h ? f : 3 * h;
+    if ((size_t)kColsumSlices * widest > need) need = (size_t)kColsumSlices * widest;
+    st->ln_partials = bp.take<float>(need * sizeof(float));
+  }
   size_t stg = h * f;
   if (h * 3 * h > stg) stg = h * 3 * h;
   if (T * h > stg) stg = T * h;
@@ -462,7 +467,7 @@ template <typename T> struct Exec {
         g.epilogue = EPI_ACCUM_F32; g.outf = st->G(l, pr.wi);
         ZB_HIP(st, gemm(st, KC_GEMM_WGRAD, g));
         ProfScope ps(st, KC_COLSUM, 0, E * T_ * pr.nout);
-        ZB_HIP(st, launch_colsum_accum<T>(pr.dy, st->G(l, pr.bi), T_, pr.nout, s));
+        ZB_HIP(st, launch_colsum_accum<T>(pr.dy, st->G(l, pr.bi), st->ln_partials, T_, pr.nout, s));
       }
     }
     return ZB_OK;

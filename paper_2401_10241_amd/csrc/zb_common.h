@@ -105,9 +105,10 @@ hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, cons
                                 hipStream_t s);
 constexpr int kLnBwdBlocks = 128;
 
-// bias gradient: db[n] += sum_rows dy[r, n]
+// bias gradient: db[n] += sum_rows dy[r, n]; scratch holds kColsumSlices * n floats
+constexpr int kColsumSlices = 8;
 template <typename T>
-hipError_t launch_colsum_accum(const T* dy, float* db, int rows, int n, hipStream_t s);
+hipError_t launch_colsum_accum(const T* dy, float* db, float* scratch, int rows, int n, hipStream_t s);
 
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_transpose_bf16(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t s);
