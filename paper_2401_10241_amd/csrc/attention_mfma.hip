@@ -22,6 +22,8 @@
 
 namespace zb {
 
+hipError_t launch_attention_fwd_d128(const AttnArgs& a, hipStream_t s);  // attention_mfma128.hip
+
 namespace {
 
 constexpr int QB = 128;  // rows owned by a workgroup (4 waves x 32)
@@ -556,7 +558,7 @@ template <typename T> hipError_t launch_attention_bwd_mfma(const AttnArgs& a, hi
 template <> hipError_t launch_attention_fwd_mfma<bf16_t>(const AttnArgs& a, hipStream_t s, bool* taken) {
   *taken = mfma_shape(a);
   if (!*taken) return hipSuccess;
-  return a.d == 64 ? run_fwd<64>(a, s) : a.d == 96 ? run_fwd<96>(a, s) : run_fwd<128>(a, s);
+  return a.d == 64 ? run_fwd<64>(a, s) : a.d == 96 ? run_fwd<96>(a, s) : launch_attention_fwd_d128(a, s);
 }
 template <> hipError_t launch_attention_bwd_mfma<bf16_t>(const AttnArgs& a, hipStream_t s, bool* taken) {
   *taken = mfma_shape(a);
