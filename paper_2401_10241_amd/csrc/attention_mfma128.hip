@@ -73,12 +73,33 @@ __device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, flo
 }
 constexpr int kWaitVm0 = 0 | (7 << 4) | (15 << 8);  // s_waitcnt vmcnt(0) only
 
+// Workgroup -> (row block, head, sample).  Consecutive workgroup ids go to different XCDs (8, each with
+// its own L2); all row blocks of one head are sent to the same XCD so that the head's K/V (or Q/dO) tiles
+// are fetched into one L2 only.  `first_heavy`: row blocks in descending order (the last query block has
+// the most keys); otherwise ascending (key block 0 sees the most queries).
+__device__ __forceinline__ void map_block(int nrb, int a, int b, bool first_heavy, int* rb, int* head, int* bi) {
+  const int id = blockIdx.x, heads = a * b;
+  int hl, r;
+  if ((heads & 7) == 0) {
+    const int xcd = id & 7, local = id >> 3;
+    hl = (local / nrb) * 8 + xcd;
+    r = local % nrb;
+  } else {
+    hl = id / nrb;
+    r = id % nrb;
+  }
+  *rb = first_heavy ? nrb - 1 - r : r;
+  *head = hl % a;
+  *bi = hl / a;
+}
+
 __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                              float* __restrict__ lse, int s, int a, float sl2) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
   bf16_t* sV = sK + 2 * TILE;                        // [2][TILE]
-  const int qb = gridDim.x - 1 - blockIdx.x, head = blockIdx.y, bi = blockIdx.z;  // heaviest blocks first
+  int qb, head, bi;
+  map_block(s / QB, a, gridDim.x / (a * (s / QB)), true, &qb, &head, &bi);  // heaviest blocks first
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
@@ -188,6 +209,262 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
   if (hi == 0) lse[((long)bi * a + head) * s + qw0 + lq] = (m + __builtin_amdgcn_logf(l)) * kLn2;
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// backward, D_i = dO_i . O_i  (one wavefront per (row, head))
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void attn_bwd128_prep_kernel(const bf16_t* __restrict__ o,
+                                                              const bf16_t* __restrict__ dout,
+                                                              float* __restrict__ dvec, int s, int a) {
+  const int i = blockIdx.x, head = blockIdx.y, bi = blockIdx.z;
+  const long off = ((long)bi * s + i) * a * D + head * D + threadIdx.x * 2;
+  float acc = (float)o[off] * (float)dout[off] + (float)o[off + 1] * (float)dout[off + 1];
+  acc = wave_sum(acc);
+  if (threadIdx.x == 0) dvec[((long)bi * a + head) * s + i] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dQ: workgroup = 128 queries, loop over key tiles up to the diagonal (same pipeline as forward)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd128_dq_kernel(const bf16_t* __restrict__ qkv,
+                                                             const bf16_t* __restrict__ dout,
+                                                             const float* __restrict__ lse,
+                                                             const float* __restrict__ dvec,
+                                                             bf16_t* __restrict__ dqkv, int s, int a, float scale) {
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [3][TILE]
+  bf16_t* sV = sK + 3 * TILE;                        // [3][TILE]
+  int qb, head, bi;
+  map_block(s / QB, a, gridDim.x / (a * (s / QB)), true, &qb, &head, &bi);
+  const int h = a * D;
+  const long ld = 3L * h;
+  const long tok0 = (long)bi * s;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int hi = lane >> 5, lq = lane & 31;
+  const int qw0 = qb * QB + wave * 32;
+  const float sl2 = scale * 1.4426950408889634f;
+
+  const int nkb = 2 * qb + 2;
+  const bf16_t* kbase = qkv + tok0 * ld + h + head * D;
+  const bf16_t* vbase = kbase + h;
+  auto issue = [&](int t) {  // 8 DMA instructions per wave
+    dma_tile(kbase + (long)t * KB * ld, ld, sK + (t % 3) * TILE, wave, lane);
+    dma_tile(vbase + (long)t * KB * ld, ld, sV + (t % 3) * TILE, wave, lane);
+  };
+  issue(0);
+  if (nkb > 1) issue(1);
+
+  bf16x8 qf[D / 16], dof[D / 16];
+  const long srow = ((long)bi * a + head) * s + qw0 + lq;
+  float lse2 = lse[srow] * 1.4426950408889634f;
+  float Dq = dvec[srow];
+  {
+    const bf16_t* qp = qkv + (tok0 + qw0 + lq) * ld + head * D + hi * 8;
+    const bf16_t* dp = dout + (tok0 + qw0 + lq) * h + head * D + hi * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+      dof[kk] = *reinterpret_cast<const bf16x8*>(dp + kk * 16);
+    }
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) asm volatile("" : "+v"(qf[kk]), "+v"(dof[kk]));
+    asm volatile("" : "+v"(lse2), "+v"(Dq));
+  }
+  f32x16 dq[D / 32];
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dq[et][v] = 0.f;
+
+  for (int jb = 0; jb < nkb; ++jb) {
+    // tile jb has landed; tile jb+1 (8 loads) may still be in flight
+    if (jb + 1 < nkb) __builtin_amdgcn_s_waitcnt(8 | (7 << 4) | (15 << 8));
+    else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __builtin_amdgcn_s_barrier();
+    if (jb + 2 < nkb) issue(jb + 2);
+    const bf16_t* kc = sK + (jb % 3) * TILE;
+    const bf16_t* vc = sV + (jb % 3) * TILE;
+    const int key0 = jb * KB;
+    if (key0 <= qw0 + 31) {
+      const bool act1 = key0 + 32 <= qw0 + 31;
+      f32x16 st[2], dpt[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[t][v] = dpt[t][v] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        st[0] = mfma(frag_rowk(kc, 0, kk, lane), qf[kk], st[0]);
+        dpt[0] = mfma(frag_rowk(vc, 0, kk, lane), dof[kk], dpt[0]);
+        if (act1) {
+          st[1] = mfma(frag_rowk(kc, 32, kk, lane), qf[kk], st[1]);
+          dpt[1] = mfma(frag_rowk(vc, 32, kk, lane), dof[kk], dpt[1]);
+        }
+      }
+      const bool diag = key0 + KB - 1 > qw0;
+      const int myq = qw0 + lq;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float p = __builtin_amdgcn_exp2f(st[t][v] * sl2 - lse2);
+          if (diag) {
+            const int key = key0 + t * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
+            if (key > myq) p = 0.f;
+          }
+          st[t][v] = p * (dpt[t][v] - Dq);
+        }
+      bf16x8 dsf[4];
+      dsf[0] = pack_half(st[0], 0); dsf[1] = pack_half(st[0], 1);
+      dsf[2] = pack_half(st[1], 0); dsf[3] = pack_half(st[1], 1);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kk < 2 || act1) {
+#pragma unroll
+          for (int et = 0; et < D / 32; ++et) dq[et] = mfma(frag_tr(kc, et * 32, kk * 16, lane), dsf[kk], dq[et]);
+        }
+      }
+    }
+  }
+  bf16_t* op = dqkv + (tok0 + qw0 + lq) * ld + head * D + hi * 4;
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      store4(op + et * 32 + g * 8, dq[et][4 * g] * scale, dq[et][4 * g + 1] * scale, dq[et][4 * g + 2] * scale,
+             dq[et][4 * g + 3] * scale);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dK and dV: workgroup = 128 keys, loop over query tiles from the diagonal to the end.
+// Per tile and wave: 4 + 4 DMA instructions for Q and dO and one 4-byte-per-lane DMA for the row
+// statistics (waves 0/1 fetch lse / D, waves 2/3 fetch the same again into a spare area so that every
+// wave has the same number of loads in flight).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd128_dkv_kernel(const bf16_t* __restrict__ qkv,
+                                                              const bf16_t* __restrict__ dout,
+                                                              const float* __restrict__ lse,
+                                                              const float* __restrict__ dvec,
+                                                              bf16_t* __restrict__ dqkv, int s, int a, float scale) {
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [3][TILE]
+  bf16_t* sO = sQ + 3 * TILE;                        // [3][TILE]  dO tiles
+  float* sS = reinterpret_cast<float*>(sO + 3 * TILE);  // [3][4][64]: lse, D, spare, spare
+  int kb, head, bi;
+  map_block(s / QB, a, gridDim.x / (a * (s / QB)), false, &kb, &head, &bi);  // key block 0 has the most work
+  const int h = a * D;
+  const long ld = 3L * h;
+  const long tok0 = (long)bi * s;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int hi = lane >> 5, lk = lane & 31;
+  const int kw0 = kb * QB + wave * 32;
+  const float sl2 = scale * 1.4426950408889634f;
+
+  const int ib0 = kb * (QB / KB), nib = s / KB;
+  const bf16_t* qbase = qkv + tok0 * ld + head * D;
+  const bf16_t* obase = dout + tok0 * h + head * D;
+  const float* stat = ((wave & 1) ? dvec : lse) + ((long)bi * a + head) * s;
+  auto issue = [&](int ib) {  // 9 DMA instructions per wave
+    const int st = (ib - ib0) % 3;
+    dma_tile(qbase + (long)ib * KB * ld, ld, sQ + st * TILE, wave, lane);
+    dma_tile(obase + (long)ib * KB * h, h, sO + st * TILE, wave, lane);
+    __builtin_amdgcn_global_load_lds((gptr_t)(stat + ib * KB + lane), (lptr_t)(sS + (st * 4 + wave) * 64), 4, 0, 0);
+  };
+  issue(ib0);
+  if (ib0 + 1 < nib) issue(ib0 + 1);
+
+  bf16x8 kf[D / 16], vf[D / 16];
+  {
+    const bf16_t* kp = qkv + (tok0 + kw0 + lk) * ld + h + head * D + hi * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      kf[kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(kp + h + kk * 16);
+    }
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) asm volatile("" : "+v"(kf[kk]), "+v"(vf[kk]));
+  }
+  f32x16 dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dk[et][v] = dv[et][v] = 0.f;
+
+  for (int ib = ib0; ib < nib; ++ib) {
+    if (ib + 1 < nib) __builtin_amdgcn_s_waitcnt(9 | (7 << 4) | (15 << 8));
+    else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __builtin_amdgcn_s_barrier();
+    if (ib + 2 < nib) issue(ib + 2);
+    const int stage = (ib - ib0) % 3;
+    const bf16_t* qc = sQ + stage * TILE;
+    const bf16_t* oc = sO + stage * TILE;
+    const float* lc = sS + stage * 256;
+    const float* dc = lc + 64;
+    const int q0 = ib * KB;
+    if (q0 + KB - 1 >= kw0) {  // some query of the tile can see this wave's keys
+      const bool act0 = q0 + 31 >= kw0;
+      f32x16 st[2], dpt[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[t][v] = dpt[t][v] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        if (act0) {
+          st[0] = mfma(frag_rowk(qc, 0, kk, lane), kf[kk], st[0]);
+          dpt[0] = mfma(frag_rowk(oc, 0, kk, lane), vf[kk], dpt[0]);
+        }
+        st[1] = mfma(frag_rowk(qc, 32, kk, lane), kf[kk], st[1]);
+        dpt[1] = mfma(frag_rowk(oc, 32, kk, lane), vf[kk], dpt[1]);
+      }
+      const bool diag = q0 < kw0 + 31;
+      const int mykey = kw0 + lk;
+      f32x16 pt[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int qi = t * 32 + g * 8 + hi * 4;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lc + qi);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dc + qi);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int v = g * 4 + i;
+            float p = __builtin_amdgcn_exp2f(st[t][v] * sl2 - l4[i] * 1.4426950408889634f);
+            if (diag && mykey > q0 + qi + i) p = 0.f;
+            if (t == 0 && !act0) p = 0.f;
+            pt[t][v] = p;
+            st[t][v] = p * (dpt[t][v] - d4[i]);
+          }
+        }
+      bf16x8 pf[4], dsf[4];
+      pf[0] = pack_half(pt[0], 0); pf[1] = pack_half(pt[0], 1);
+      pf[2] = pack_half(pt[1], 0); pf[3] = pack_half(pt[1], 1);
+      dsf[0] = pack_half(st[0], 0); dsf[1] = pack_half(st[0], 1);
+      dsf[2] = pack_half(st[1], 0); dsf[3] = pack_half(st[1], 1);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kk >= 2 || act0) {
+#pragma unroll
+          for (int et = 0; et < D / 32; ++et) {
+            dv[et] = mfma(frag_tr(oc, et * 32, kk * 16, lane), pf[kk], dv[et]);
+            dk[et] = mfma(frag_tr(qc, et * 32, kk * 16, lane), dsf[kk], dk[et]);
+          }
+        }
+      }
+    }
+  }
+  bf16_t* kp = dqkv + (tok0 + kw0 + lk) * ld + h + head * D + hi * 4;
+#pragma unroll
+  for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      store4(kp + et * 32 + g * 8, dk[et][4 * g] * scale, dk[et][4 * g + 1] * scale, dk[et][4 * g + 2] * scale,
+             dk[et][4 * g + 3] * scale);
+      store4(kp + h + et * 32 + g * 8, dv[et][4 * g], dv[et][4 * g + 1], dv[et][4 * g + 2], dv[et][4 * g + 3]);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_attention_fwd_d128(const AttnArgs& a, hipStream_t s) {
@@ -199,9 +476,37 @@ hipError_t launch_attention_fwd_d128(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     done = true;
   }
-  dim3 grid(a.s / QB, a.a, a.b);
+  dim3 grid((a.s / QB) * a.a * a.b);
   attn_fwd128_kernel<<<grid, 256, smem, s>>>((const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.s, a.a,
                                              1.4426950408889634f / sqrtf((float)D));
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bwd_d128(const AttnArgs& a, hipStream_t s) {
+  static bool done = false;
+  constexpr size_t smem_q = (size_t)6 * TILE * sizeof(bf16_t);
+  constexpr size_t smem_kv = smem_q + 3 * 4 * 64 * sizeof(float);
+  if (!done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dq_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_q);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dkv_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_kv);
+    if (e != hipSuccess) return e;
+    done = true;
+  }
+  const float scale = 1.0f / sqrtf((float)D);
+  dim3 grid1(a.s, a.a, a.b);
+  attn_bwd128_prep_kernel<<<grid1, 64, 0, s>>>((const bf16_t*)a.o, (const bf16_t*)a.dout, a.dvec, a.s, a.a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 grid((a.s / QB) * a.a * a.b);
+  attn_bwd128_dq_kernel<<<grid, 256, smem_q, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
+                                                  (bf16_t*)a.dqkv, a.s, a.a, scale);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  attn_bwd128_dkv_kernel<<<grid, 256, smem_kv, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
+                                                    (bf16_t*)a.dqkv, a.s, a.a, scale);
   return hipGetLastError();
 }
 
