@@ -81,9 +81,10 @@ __device__ __forceinline__ void map_block(int nrb, int a, int b, bool first_heav
   const int id = blockIdx.x, heads = a * b;
   int hl, r;
   if ((heads & 7) == 0) {
-    const int xcd = id & 7, local = id >> 3;
-    hl = (local / nrb) * 8 + xcd;
-    r = local % nrb;
+    // within an XCD: heaviest row blocks of all its heads first, so the light ones fill the tail
+    const int xcd = id & 7, local = id >> 3, hpx = heads >> 3;
+    hl = (local % hpx) * 8 + xcd;
+    r = local / hpx;
   } else {
     hl = id / nrb;
     r = id % nrb;
@@ -226,14 +227,14 @@ __global__ __launch_bounds__(64) void attn_bwd128_prep_kernel(const bf16_t* __re
 // ------------------------------------------------------------------------------------------------
 // backward, dQ: workgroup = 128 queries, loop over key tiles up to the diagonal (same pipeline as forward)
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_bwd128_dq_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_bwd128_dq_kernel(const bf16_t* __restrict__ qkv,
                                                              const bf16_t* __restrict__ dout,
                                                              const float* __restrict__ lse,
                                                              const float* __restrict__ dvec,
                                                              bf16_t* __restrict__ dqkv, int s, int a, float scale) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [3][TILE]
-  bf16_t* sV = sK + 3 * TILE;                        // [3][TILE]
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
+  bf16_t* sV = sK + 2 * TILE;                        // [2][TILE]
   int qb, head, bi;
   map_block(s / QB, a, gridDim.x / (a * (s / QB)), true, &qb, &head, &bi);
   const int h = a * D;
@@ -248,11 +249,10 @@ __global__ __launch_bounds__(256) void attn_bwd128_dq_kernel(const bf16_t* __res
   const bf16_t* kbase = qkv + tok0 * ld + h + head * D;
   const bf16_t* vbase = kbase + h;
   auto issue = [&](int t) {  // 8 DMA instructions per wave
-    dma_tile(kbase + (long)t * KB * ld, ld, sK + (t % 3) * TILE, wave, lane);
-    dma_tile(vbase + (long)t * KB * ld, ld, sV + (t % 3) * TILE, wave, lane);
+    dma_tile(kbase + (long)t * KB * ld, ld, sK + (t & 1) * TILE, wave, lane);
+    dma_tile(vbase + (long)t * KB * ld, ld, sV + (t & 1) * TILE, wave, lane);
   };
   issue(0);
-  if (nkb > 1) issue(1);
 
   bf16x8 qf[D / 16], dof[D / 16];
   const long srow = ((long)bi * a + head) * s + qw0 + lq;
@@ -277,13 +277,11 @@ __global__ __launch_bounds__(256) void attn_bwd128_dq_kernel(const bf16_t* __res
     for (int v = 0; v < 16; ++v) dq[et][v] = 0.f;
 
   for (int jb = 0; jb < nkb; ++jb) {
-    // tile jb has landed; tile jb+1 (8 loads) may still be in flight
-    if (jb + 1 < nkb) __builtin_amdgcn_s_waitcnt(8 | (7 << 4) | (15 << 8));
-    else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);  // tile jb has landed
     __builtin_amdgcn_s_barrier();
-    if (jb + 2 < nkb) issue(jb + 2);
-    const bf16_t* kc = sK + (jb % 3) * TILE;
-    const bf16_t* vc = sV + (jb % 3) * TILE;
+    if (jb + 1 < nkb) issue(jb + 1);
+    const bf16_t* kc = sK + (jb & 1) * TILE;
+    const bf16_t* vc = sV + (jb & 1) * TILE;
     const int key0 = jb * KB;
     if (key0 <= qw0 + 31) {
       const bool act1 = key0 + 32 <= qw0 + 31;
@@ -484,8 +482,8 @@ hipError_t launch_attention_fwd_d128(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attention_bwd_d128(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
-  constexpr size_t smem_q = (size_t)6 * TILE * sizeof(bf16_t);
-  constexpr size_t smem_kv = smem_q + 3 * 4 * 64 * sizeof(float);
+  constexpr size_t smem_q = (size_t)4 * TILE * sizeof(bf16_t);
+  constexpr size_t smem_kv = (size_t)6 * TILE * sizeof(bf16_t) + 3 * 4 * 64 * sizeof(float);
   if (!done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dq_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_q);
