@@ -202,13 +202,16 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
     if (it + BS - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::allowed(parity)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
-    issue(it);
+    // The refill of the stage that step it-1 used may be issued any time after the barrier; with the deep
+    // ring it goes after the fragment reads so that the matrix pipe gets its work first.
+    if constexpr (!XBAR) issue(it);  // shallow ring, two workgroups per CU: refill at once
     bf16x8 af0[MT], bf0[NT];
     load_frags(it, parity, 0, af0, bf0);
     if constexpr (XBAR) {
       if (it > 0) mfmas(af1, bf1);  // second half of tile it-1
       mfmas(af0, bf0);
       load_frags(it, parity, 1, af1, bf1);
+      issue(it);
       // these LDS reads must have completed before the next barrier lets another wave refill the stage
       __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
     } else {
