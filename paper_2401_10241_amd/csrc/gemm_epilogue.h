@@ -49,7 +49,10 @@ __device__ __forceinline__ void epilogue_tile(const EpiParams& e, int m0, int n,
   size_t idx[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) idx[v] = (size_t)(m0 + (v >> 2) * 8 + (v & 3)) * e.N + n;
-  if (MODE == EPI_ACCUM_F32) {
+  if (MODE == EPI_PARTIAL) {  // e.outf already points at this K slice's [M,N] plane
+#pragma unroll
+    for (int v = 0; v < 16; ++v) e.outf[idx[v]] = acc[v];
+  } else if (MODE == EPI_ACCUM_F32) {
     float c[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) c[v] = e.outf[idx[v]];

@@ -127,7 +127,7 @@ template <int BM, int BS, bool ATR> struct Cfg {
 template <int BM, int BS, bool ATR, int MODE>
 __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ B, int M, int N, int K,
-                                                            long lda, long ldb, EpiParams epi) {
+                                                            long lda, long ldb, EpiParams epi, int ksplit) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   typedef Cfg<BM, BS, ATR> C;
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
@@ -141,6 +141,19 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   const int nblk = gridDim.x;
   int pid = blockIdx.x;
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  if constexpr (MODE == EPI_PARTIAL) {
+    // split-K: the K range is cut into ksplit slices of whole 64-k blocks; slice s of every tile writes its
+    // fp32 partial product to plane s of the workspace (a fix-up kernel adds the planes in order)
+    const int tiles = nblk / ksplit;
+    const int slice = pid / tiles;
+    pid -= slice * tiles;
+    const int blocks64 = K / 64, per = (blocks64 + ksplit - 1) / ksplit;
+    const int kb0 = slice * per, kb1 = min(blocks64, kb0 + per);
+    A += (long)kb0 * 64;          // K-contiguous A
+    B += (long)kb0 * 64 * ldb;    // row-contiguous B
+    K = (kb1 - kb0) * 64;
+    epi.outf += (size_t)slice * M * N;
+  }
   const int m0 = (pid % tiles_m) * BM;
   const int n0 = (pid / tiles_m) * BN;
 
@@ -239,7 +252,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
 }
 
 template <int BM, int BS, bool ATR, int MODE>
-hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s) {
+hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s, int ksplit = 1) {
   auto kern = gemm_mfma_kernel<BM, BS, ATR, MODE>;
   constexpr size_t smem = Cfg<BM, BS, ATR>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget");
@@ -250,14 +263,81 @@ hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int grid = (g.M / BM) * (g.N / BN);
-  kern<<<grid, NTHREADS, smem, s>>>((const bf16_t*)g.A, (const bf16_t*)g.B, g.M, g.N, g.K, lda, ldb, make_epi(g));
+  const int grid = (g.M / BM) * (g.N / BN) * ksplit;
+  kern<<<grid, NTHREADS, smem, s>>>((const bf16_t*)g.A, (const bf16_t*)g.B, g.M, g.N, g.K, lda, ldb, make_epi(g),
+                                    ksplit);
   return hipGetLastError();
+}
+
+// Split-K fix-up: out = epilogue(sum of the K-slice planes, added in slice order), 4 columns per thread.
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_splitk_fixup_kernel(const float* __restrict__ ws, int slices, size_t plane,
+                                                                int N, EpiParams epi) {
+  const size_t i4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i4 >= plane) return;
+  f32x4 acc = *reinterpret_cast<const f32x4*>(ws + i4);
+  for (int sl = 1; sl < slices; ++sl) acc += *reinterpret_cast<const f32x4*>(ws + (size_t)sl * plane + i4);
+  const int n = (int)(i4 % (size_t)N);
+  bf16x4 o0, o1;
+  if (MODE == EPI_STORE) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o0[e] = (bf16_t)acc[e];
+  } else if (MODE == EPI_DGELU) {
+    const bf16x4 a = *reinterpret_cast<const bf16x4*>((const bf16_t*)epi.aux + i4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o0[e] = (bf16_t)(acc[e] * gelu_grad_f((float)a[e]));
+  } else {
+    const f32x4 b = *reinterpret_cast<const f32x4*>(epi.bias + n);
+    if (MODE == EPI_BIAS_RESID) {
+      const bf16x4 a = *reinterpret_cast<const bf16x4*>((const bf16_t*)epi.aux + i4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o0[e] = (bf16_t)(acc[e] + b[e] + (float)a[e]);
+    } else if (MODE == EPI_BIAS_GELU) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float f = acc[e] + b[e];
+        o0[e] = (bf16_t)f;
+        o1[e] = (bf16_t)gelu_f(f);
+      }
+      *reinterpret_cast<bf16x4*>((bf16_t*)epi.out1 + i4) = o1;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o0[e] = (bf16_t)(acc[e] + b[e]);
+    }
+  }
+  *reinterpret_cast<bf16x4*>((bf16_t*)epi.out0 + i4) = o0;
+}
+
+// Few tiles and a long K (the N = hidden GEMMs of a 1024-token microbatch): cut K into slices so that
+// every CU gets a workgroup.  Returns false if the shape is not one for split-K.
+template <int MODE>
+bool try_split_k(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipError_t* err) {
+  if (g.M % 256 != 0 || g.N % BN != 0 || g.N % 4 != 0 || g.K < 4096 || !g.workspace) return false;
+  const long tiles = (long)(g.M / 256) * (g.N / BN);
+  if (tiles > 128) return false;
+  int slices = (int)(256 / tiles);
+  if (slices > 4) slices = 4;
+  const size_t plane = (size_t)g.M * g.N;
+  if (slices < 2 || (size_t)slices * plane > g.workspace_floats) return false;
+  GemmArgs p = g;
+  p.epilogue = EPI_PARTIAL;
+  p.outf = g.workspace;
+  *err = run_cfg<256, 5, false, EPI_PARTIAL>(p, lda, ldb, s, slices);
+  if (*err != hipSuccess) return true;
+  const size_t threads = plane / 4;
+  gemm_splitk_fixup_kernel<MODE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(g.workspace, slices, plane, g.N,
+                                                                                 make_epi(g));
+  *err = hipGetLastError();
+  return true;
 }
 
 template <bool ATR, int MODE>
 hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool* taken) {
   *taken = true;
+  if constexpr (!ATR) {
+    hipError_t e = hipSuccess;
+    if (try_split_k<MODE>(g, lda, ldb, s, &e)) return e;
+  }
   if (g.N % BN == 0) {
     // Rounds of tiles over the 256 CUs times the tile height; the taller tile does about 1.25x the
     // work per cycle, so it wins only when it does not cost an extra, mostly empty round.

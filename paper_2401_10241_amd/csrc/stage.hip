@@ -80,8 +80,8 @@ struct zb_stage {
   int m = 0, iter = 0;
 
   char* tmp = nullptr;  // [T, h] activation-gradient scratch
-  float *dvec = nullptr, *ln_partials = nullptr, *staging = nullptr;
-  size_t staging_floats = 0;
+  float *dvec = nullptr, *ln_partials = nullptr, *staging = nullptr, *gemm_ws = nullptr;
+  size_t staging_floats = 0, gemm_ws_floats = 0;
   double* partial_sq = nullptr;
   int* partial_nf = nullptr;
   OptDevState* opt = nullptr;
@@ -240,6 +240,10 @@ size_t layout(zb_stage* st, void* arena) {
   if (T * h > stg) stg = T * h;
   st->staging_floats = stg;
   st->staging = bp.take<float>(stg * sizeof(float));
+  if (st->bf16) {  // split-K partial products of the N = hidden GEMMs (up to 4 K slices)
+    st->gemm_ws_floats = (size_t)4 * T * h;
+    st->gemm_ws = bp.take<float>(st->gemm_ws_floats * sizeof(float));
+  }
   st->partial_sq = bp.take<double>(kSumsqBlocks * sizeof(double));
   st->partial_nf = bp.take<int>(kSumsqBlocks * sizeof(int));
   st->opt = bp.take<OptDevState>(sizeof(OptDevState));
@@ -309,7 +313,9 @@ template <typename T> struct Exec {
     }
   }
 
-  static hipError_t gemm(zb_stage* st, int cls, const GemmArgs& g) {
+  static hipError_t gemm(zb_stage* st, int cls, GemmArgs g) {
+    g.workspace = st->gemm_ws;
+    g.workspace_floats = st->gemm_ws_floats;
     double bytes = 0;
     const double E = sizeof(T);
     if (g.epilogue == EPI_ACCUM_F32) bytes = 8.0 * g.M * g.N + E * (double)g.K * ((double)g.M + g.N);

@@ -57,7 +57,8 @@ enum Epilogue : int {
   EPI_BIAS_RESID = 2,  // out0 = acc + bias[n] + resid[m,n]
   EPI_BIAS_GELU = 3,   // out0 = acc + bias[n]; out1 = gelu(out0)
   EPI_DGELU = 4,       // out0 = acc * gelu'(aux[m,n])
-  EPI_ACCUM_F32 = 5    // outf[m,n] += acc   (fp32 gradient accumulation)
+  EPI_ACCUM_F32 = 5,   // outf[m,n] += acc   (fp32 gradient accumulation)
+  EPI_PARTIAL = 6      // internal: fp32 partial product of one K slice (split-K), finished by a fix-up kernel
 };
 
 struct GemmArgs {
@@ -71,6 +72,8 @@ struct GemmArgs {
   float* outf;         // fp32 [M,N] (EPI_ACCUM_F32)
   const float* bias;   // [N] fp32
   const void* aux;     // resid or pre-activation, [M,N] type T
+  float* workspace;    // optional fp32 scratch for split-K partial products (device), may be null
+  size_t workspace_floats;
 };
 
 template <typename T> hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);

@@ -67,6 +67,13 @@ def test_mfma_attention_shapes(d, heads, seq, b):
     run_and_compare(w)
 
 
+def test_split_k_gemm_shapes():
+    # few output tiles and a long contraction (hidden 2048, ffn 8192, 256 tokens): the N = hidden GEMMs
+    # run as K slices plus a fix-up kernel
+    w = W("splitk", "bf16", 1, 2048, 16, 8192, 256, 1, 2, 1, 2, "H1", seed=77)
+    run_and_compare(w)
+
+
 def test_accumulation_is_bitwise_identical_across_orders():
     import paper_2401_10241_amd as zb
     w = W("det", "bf16", 2, 256, 4, 1024, 128, 1, 4, 1, 8, "H1", seed=21)
