@@ -23,25 +23,22 @@ PEAK_FP32_TFLOPS = 157.3    # fp32 vector
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(w, seconds_hint=20.0):
+def cpu_baseline(w):
     """The oracle, as it stands, timed on the host cores on a bounded sample of the same workload:
-    one microbatch's F + B + W through ONE layer of the workload's shape."""
-    import numpy as np
+    ONE microbatch's F + B + W through all layers of the stage (1/m of the step's passes, no optimizer)."""
     import zb_inputs
     from oracle.stage import StageOracle
     from oracle.schedule import F, B, W
-    w1 = w.scaled(layers=1)
-    params = zb_inputs.stage_params(w1)
-    orc = StageOracle(layers=1, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
-                      dtype=w.dtype, params=params)
+    orc = StageOracle(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+                      dtype=w.dtype, params=zb_inputs.stage_params(w))
     orc.begin_iteration(1)
-    orc.set_input(0, zb_inputs.stage_input(w1, 0, 0))
-    orc.set_upstream_grad(0, zb_inputs.upstream_grad(w1, 0, 0))
+    orc.set_input(0, zb_inputs.stage_input(w, 0, 0))
+    orc.set_upstream_grad(0, zb_inputs.upstream_grad(w, 0, 0))
     t0 = time.perf_counter()
     orc.run([(F, 0), (B, 0), (W, 0)])
     dt = time.perf_counter() - t0
     s, b, h = w.seq, w.mb_size, w.hidden
-    flops = s * b * h * (72 * h + 12 * s)
+    flops = w.layers * s * b * h * (72 * h + 12 * s)
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
@@ -52,8 +49,21 @@ def cpu_baseline(w, seconds_hint=20.0):
             break
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "seconds": round(dt, 3),
-            "sample": f"numpy fp64 oracle, 1 microbatch F+B+W through 1 of the {w.layers} layers of {w.name} "
-                      f"({flops / 1e12:.2f} TFLOP of the step's {w.layers * w.m * flops / 1e12:.0f})"}
+            "sample": f"numpy fp64 oracle, 1 of the {w.m} microbatches: F+B+W through the {w.layers} layers of "
+                      f"{w.name} ({flops / 1e12:.2f} TFLOP of the step's {w.m * flops / 1e12:.0f})"}
+
+
+def measured_traffic(workload):
+    """HBM bytes per GEMM launch from the rocprofv3 counter runs summarised under profiles/ (FETCH_SIZE and
+    WRITE_SIZE, each scaled by its reading for a plain copy of known size); None if no summary is there."""
+    path = os.path.join(ROOT, "profiles", f"gemm_hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -65,6 +75,9 @@ def main():
     ap.add_argument("--m", type=int, default=0, help="override the number of microbatches (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (calibrates FETCH_SIZE / WRITE_SIZE "
+                         "in a rocprofv3 --pmc run of this command)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build covers one pipeline stage on ONE GPU; --gpus above 1 is not supported "
@@ -102,6 +115,15 @@ def main():
         st.run_schedule(w.p, w.stage, m, w.kind)
         if w.optimizer:
             st.optimizer_step_validated(0.0, zb_inputs.rest_state(w, it), want_report=False)
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     for _ in range(args.warmup):
         step()
@@ -144,11 +166,14 @@ def main():
         g_ms = sum(r["total_ms"] for r in gemm)
         g_fl = sum(r["flops"] for r in gemm)
         g_n = sum(r["launches"] for r in gemm)
+        g_by = sum(r["bytes"] for r in gemm)
         peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
         ach = g_fl / g_ms / 1e9
         out["roofline"] = {"kernel": "GEMM kernels (forward, dgrad, wgrad launches of one profiled step)",
                            "bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": round(ach, 1),
-                           "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4), "traffic": None,
+                           "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4),
+                           "traffic": measured_traffic(w.name) if not args.m else None,
+                           "algorithmic_bytes_per_launch": g_by / g_n,
                            "launches": g_n, "avg_launch_us": round(1e3 * g_ms / g_n, 2),
                            "flops_per_launch": g_fl / g_n,
                            "share_of_step_kernel_time": round(g_ms / sum(r["total_ms"] for r in stats), 3)}

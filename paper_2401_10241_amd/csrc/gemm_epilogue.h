@@ -6,7 +6,7 @@ namespace zb {
 
 struct EpiParams {
   int mode;
-  int N;
+  int N;  // row stride of the outputs, aux and outf (elements)
   void* out0;
   void* out1;
   float* outf;

@@ -154,8 +154,16 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
     K = (kb1 - kb0) * 64;
     epi.outf += (size_t)slice * M * N;
   }
-  const int m0 = (pid % tiles_m) * BM;
-  const int n0 = (pid / tiles_m) * BN;
+  // Tiles are walked in bands of GROUP_M tile rows, M fastest within a band: the 64 or so workgroups that
+  // an XCD runs at one time then cover a block of about GROUP_M x 8 tiles and share, through its L2, both
+  // the A panels (8 ways) and the B panels (GROUP_M ways) instead of streaming all of A once per column.
+  constexpr int GROUP_M = 8;
+  const int tiles_n = N / BN;
+  const int band = pid / (GROUP_M * tiles_n);
+  const int band_rows = min(tiles_m - band * GROUP_M, GROUP_M);
+  const int in_band = pid - band * GROUP_M * tiles_n;
+  const int m0 = (band * GROUP_M + in_band % band_rows) * BM;
+  const int n0 = (in_band / band_rows) * BN;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
@@ -251,8 +259,9 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
     }
 }
 
+// ldo: row stride of the outputs when the GEMM covers a column range of a wider matrix (0: g.N)
 template <int BM, int BS, bool ATR, int MODE>
-hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s, int ksplit = 1) {
+hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s, int ksplit = 1, int ldo = 0) {
   auto kern = gemm_mfma_kernel<BM, BS, ATR, MODE>;
   constexpr size_t smem = Cfg<BM, BS, ATR>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget");
@@ -264,20 +273,23 @@ hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s, int ksp
     attr_set = true;
   }
   const int grid = (g.M / BM) * (g.N / BN) * ksplit;
-  kern<<<grid, NTHREADS, smem, s>>>((const bf16_t*)g.A, (const bf16_t*)g.B, g.M, g.N, g.K, lda, ldb, make_epi(g),
-                                    ksplit);
+  EpiParams epi = make_epi(g);
+  if (ldo) epi.N = ldo;
+  kern<<<grid, NTHREADS, smem, s>>>((const bf16_t*)g.A, (const bf16_t*)g.B, g.M, g.N, g.K, lda, ldb, epi, ksplit);
   return hipGetLastError();
 }
 
 // Split-K fix-up: out = epilogue(sum of the K-slice planes, added in slice order), 4 columns per thread.
+// The planes are [M, N] dense; the outputs (and aux) have row stride epi.N >= N.
 template <int MODE>
 __global__ __launch_bounds__(256) void gemm_splitk_fixup_kernel(const float* __restrict__ ws, int slices, size_t plane,
                                                                 int N, EpiParams epi) {
-  const size_t i4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i4 >= plane) return;
-  f32x4 acc = *reinterpret_cast<const f32x4*>(ws + i4);
-  for (int sl = 1; sl < slices; ++sl) acc += *reinterpret_cast<const f32x4*>(ws + (size_t)sl * plane + i4);
-  const int n = (int)(i4 % (size_t)N);
+  const size_t p4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (p4 >= plane) return;
+  f32x4 acc = *reinterpret_cast<const f32x4*>(ws + p4);
+  for (int sl = 1; sl < slices; ++sl) acc += *reinterpret_cast<const f32x4*>(ws + (size_t)sl * plane + p4);
+  const int n = (int)(p4 % (size_t)N);
+  const size_t i4 = (p4 / (size_t)N) * (size_t)epi.N + n;
   bf16x4 o0, o1;
   if (MODE == EPI_STORE) {
 #pragma unroll
@@ -331,12 +343,54 @@ bool try_split_k(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipError_
   return true;
 }
 
+// A little more than a whole number of rounds of 256 x 256 tiles over the 256 CUs (N = ffn with 1024
+// tokens: 320 tiles): the full rounds run as they are and the tile columns left over are cut along K so
+// that they, too, fill every CU once instead of occupying a quarter of the chip for a whole round.
+template <int MODE>
+bool try_tail_split(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipError_t* err) {
+  if (g.M % 256 != 0 || g.N % BN != 0 || g.K < 2048 || !g.workspace) return false;
+  const int tm = g.M / 256, tn = g.N / BN;
+  if ((long)tm * tn <= 256 || tm > 256 || 256 % tm != 0) return false;
+  const int cols_per_round = 256 / tm;
+  const int tail_cols = tn % cols_per_round;
+  if (tail_cols == 0 || tail_cols * tm > 128) return false;
+  int slices = 256 / (tail_cols * tm);
+  if (slices > 4) slices = 4;
+  const int n_main = (tn - tail_cols) * BN, n_tail = tail_cols * BN;
+  const size_t plane = (size_t)g.M * n_tail;
+  if ((size_t)slices * plane > g.workspace_floats) return false;
+  GemmArgs a = g;
+  a.N = n_main;
+  *err = run_cfg<256, 5, false, MODE>(a, lda, ldb, s, 1, g.N);
+  if (*err != hipSuccess) return true;
+  GemmArgs t = g;  // the same GEMM on columns n_main .. N-1
+  t.N = n_tail;
+  t.B = (const bf16_t*)g.B + n_main;
+  if (t.out0) t.out0 = (bf16_t*)g.out0 + n_main;
+  if (t.out1) t.out1 = (bf16_t*)g.out1 + n_main;
+  if (t.aux) t.aux = (const bf16_t*)g.aux + n_main;
+  if (t.bias) t.bias = g.bias + n_main;
+  GemmArgs p = t;
+  p.epilogue = EPI_PARTIAL;
+  p.outf = g.workspace;
+  *err = run_cfg<256, 5, false, EPI_PARTIAL>(p, lda, ldb, s, slices);
+  if (*err != hipSuccess) return true;
+  EpiParams epi = make_epi(t);
+  epi.N = g.N;
+  const size_t threads = plane / 4;
+  gemm_splitk_fixup_kernel<MODE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(g.workspace, slices, plane, n_tail,
+                                                                                 epi);
+  *err = hipGetLastError();
+  return true;
+}
+
 template <bool ATR, int MODE>
 hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool* taken) {
   *taken = true;
   if constexpr (!ATR) {
     hipError_t e = hipSuccess;
     if (try_split_k<MODE>(g, lda, ldb, s, &e)) return e;
+    if (try_tail_split<MODE>(g, lda, ldb, s, &e)) return e;
   }
   if (g.N % BN == 0) {
     // Rounds of tiles over the 256 CUs times the tile height; the taller tile does about 1.25x the

@@ -74,6 +74,13 @@ def test_split_k_gemm_shapes():
     run_and_compare(w)
 
 
+def test_tail_split_gemm_shapes():
+    # 1024 tokens x ffn 16896: 4 x 66 tiles of 256 x 256, two tile columns more than one round over the 256
+    # CUs; those columns run as K slices plus a fix-up kernel writing a column range of the output
+    w = W("tailsplit", "bf16", 1, 2048, 16, 16896, 1024, 1, 2, 1, 1, "H1", seed=78)
+    run_and_compare(w)
+
+
 def test_accumulation_is_bitwise_identical_across_orders():
     import paper_2401_10241_amd as zb
     w = W("det", "bf16", 2, 256, 4, 1024, 128, 1, 4, 1, 8, "H1", seed=21)
