@@ -109,82 +109,98 @@ __device__ __forceinline__ void block_sum2(float& a, float& b, float (*red)[2]) 
   b = (red[0][1] + red[1][1]) + (red[2][1] + red[3][1]);
 }
 
-// Each workgroup walks rows blockIdx.x, blockIdx.x + gridDim.x, ... and keeps per-column partial
-// sums of g*xhat and g in registers; they are written to partials[block][0/1][h].  The next row's
-// operands are fetched while the current row is reduced.  NCH = ceil(h / 1024) chunks of 4 per lane.
+// dx of one row per workgroup: dx = resid + rstd * (g*gamma - mean(g*gamma) - xhat * mean(g*gamma*xhat)).
+// NCH = ceil(h / 1024) chunks of 4 per lane; the whole row stays in registers between the two passes.
 template <typename T, int NCH>
-__global__ __launch_bounds__(kThreads) void layernorm_bwd_kernel(const T* __restrict__ g, const T* __restrict__ x,
-                                                                 const float* __restrict__ stats,
-                                                                 const float* __restrict__ gamma,
-                                                                 const T* __restrict__ resid, T* __restrict__ dx,
-                                                                 float* __restrict__ partials, int rows, int h) {
+__global__ __launch_bounds__(kThreads) void layernorm_bwd_dx_kernel(const T* __restrict__ g, const T* __restrict__ x,
+                                                                    const float* __restrict__ stats,
+                                                                    const float* __restrict__ gamma,
+                                                                    const T* __restrict__ resid, T* __restrict__ dx,
+                                                                    int h) {
   __shared__ float red[4][2];
-  float gam[NCH][kVec], pg[NCH][kVec], pb[NCH][kVec];
-#pragma unroll
-  for (int c = 0; c < NCH; ++c) {
-    const int col = (c * kThreads + threadIdx.x) * kVec;
-    if (col < h) Vec4<float>::load(gamma + col, gam[c]);
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) pg[c][e] = pb[c][e] = 0.f;
-  }
-  float gv[NCH][kVec], xv[NCH][kVec], rv[NCH][kVec];
-  auto fetch = [&](int row) {
-    const size_t off = (size_t)row * h;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      const int col = (c * kThreads + threadIdx.x) * kVec;
-      if (col < h) {
-        Vec4<T>::load(g + off + col, gv[c]);
-        Vec4<T>::load(x + off + col, xv[c]);
-        Vec4<T>::load(resid + off + col, rv[c]);
-      }
-    }
-  };
-  int row = blockIdx.x;
-  if (row < rows) fetch(row);
-  for (; row < rows; row += gridDim.x) {
-    const size_t off = (size_t)row * h;
-    const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
-    float gg[NCH][kVec], xh[NCH][kVec], rr[NCH][kVec];
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      const int col = (c * kThreads + threadIdx.x) * kVec;
-      if (col < h) {
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-          xh[c][e] = (xv[c][e] - mean) * rstd;
-          pg[c][e] += gv[c][e] * xh[c][e];
-          pb[c][e] += gv[c][e];
-          gg[c][e] = gv[c][e] * gam[c][e];
-          rr[c][e] = rv[c][e];
-          s1 += gg[c][e];
-          s2 += gg[c][e] * xh[c][e];
-        }
-      }
-    }
-    if (row + (int)gridDim.x < rows) fetch(row + gridDim.x);
-    block_sum2(s1, s2, red);
-    const float m1 = s1 / (float)h, m2 = s2 / (float)h;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      const int col = (c * kThreads + threadIdx.x) * kVec;
-      if (col < h) {
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) o[e] = rr[c][e] + rstd * (gg[c][e] - m1 - xh[c][e] * m2);
-        Vec4<T>::store(dx + off + col, o);
-      }
-    }
-  }
-  float* p0 = partials + (size_t)blockIdx.x * 2 * h;
+  const int row = blockIdx.x;
+  const size_t off = (size_t)row * h;
+  const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+  float gg[NCH][kVec], xh[NCH][kVec], rr[NCH][kVec];
+  float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int col = (c * kThreads + threadIdx.x) * kVec;
     if (col < h) {
-      Vec4<float>::store(p0 + col, pg[c]);
-      Vec4<float>::store(p0 + h + col, pb[c]);
+      float gam[kVec];
+      Vec4<T>::load(g + off + col, gg[c]);
+      Vec4<T>::load(x + off + col, xh[c]);
+      Vec4<T>::load(resid + off + col, rr[c]);
+      Vec4<float>::load(gamma + col, gam);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) {
+        xh[c][e] = (xh[c][e] - mean) * rstd;
+        gg[c][e] *= gam[e];
+        s1 += gg[c][e];
+        s2 += gg[c][e] * xh[c][e];
+      }
     }
+  }
+  block_sum2(s1, s2, red);
+  const float m1 = s1 / (float)h, m2 = s2 / (float)h;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) o[e] = rr[c][e] + rstd * (gg[c][e] - m1 - xh[c][e] * m2);
+      Vec4<T>::store(dx + off + col, o);
+    }
+  }
+}
+
+// Column sums of g*xhat and g over one slice of rows: partials[slice][0][h] and partials[slice][1][h].
+// 256 threads = 16 column-lanes (8 consecutive columns each) x 16 row groups; grid.y = row slices.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void layernorm_bwd_param_kernel(const T* __restrict__ g,
+                                                                       const T* __restrict__ x,
+                                                                       const float* __restrict__ stats,
+                                                                       float* __restrict__ partials, int rows, int h,
+                                                                       int rows_per_slice) {
+  __shared__ float red[2][16][129];
+  const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
+  const int col = (blockIdx.x * 16 + cl) * 8;
+  const int r_begin = blockIdx.y * rows_per_slice;
+  const int r_end = min(rows, r_begin + rows_per_slice);
+  float ag[8], ab[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ag[e] = ab[e] = 0.f;
+  for (int r = r_begin + rg; r < r_end; r += 16) {
+    const float mean = stats[r * 2], rstd = stats[r * 2 + 1];
+    const size_t off = (size_t)r * h + col;
+#pragma unroll
+    for (int q = 0; q < 8; q += 4) {
+      if (col + q < h) {
+        float gv[4], xv[4];
+        Vec4<T>::load(g + off + q, gv);
+        Vec4<T>::load(x + off + q, xv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          ag[q + e] += gv[e] * ((xv[e] - mean) * rstd);
+          ab[q + e] += gv[e];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    red[0][rg][cl * 8 + e] = ag[e];
+    red[1][rg][cl * 8 + e] = ab[e];
+  }
+  __syncthreads();
+  const int which = threadIdx.x >> 7, t = threadIdx.x & 127;
+  const int c = blockIdx.x * 128 + t;
+  if (c < h) {
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += red[which][r][t];
+    partials[((size_t)blockIdx.y * 2 + which) * h + c] = sum;
   }
 }
 
@@ -313,9 +329,9 @@ hipError_t launch_layernorm_fwd(const T* x, const float* gamma, const float* bet
 }
 
 template <typename T, int NCH>
-hipError_t run_ln_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid, T* dx,
-                      float* partials, int rows, int h, int blocks, hipStream_t s) {
-  layernorm_bwd_kernel<T, NCH><<<blocks, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, partials, rows, h);
+hipError_t run_ln_bwd_dx(const T* g, const T* x, const float* stats, const float* gamma, const T* resid, T* dx,
+                         int rows, int h, hipStream_t s) {
+  layernorm_bwd_dx_kernel<T, NCH><<<rows, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, h);
   return hipGetLastError();
 }
 
@@ -324,20 +340,26 @@ hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, cons
                                 T* dx, float* dgamma, float* dbeta, float* partials, int rows, int h,
                                 hipStream_t s) {
   if (h % kVec != 0 || h > kThreads * kVec * kMaxChunks || rows <= 0) return hipErrorInvalidValue;
-  const int blocks = rows < kLnBwdBlocks ? rows : kLnBwdBlocks;
   const int nch = (h + kThreads * kVec - 1) / (kThreads * kVec);
   hipError_t e;
   switch (nch) {
-    case 1: e = run_ln_bwd<T, 1>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
-    case 2: e = run_ln_bwd<T, 2>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
-    case 3: e = run_ln_bwd<T, 3>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
-    case 4: e = run_ln_bwd<T, 4>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
-    case 5: e = run_ln_bwd<T, 5>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
-    case 6: e = run_ln_bwd<T, 6>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
-    default: e = run_ln_bwd<T, 8>(g, x, stats, gamma, resid, dx, partials, rows, h, blocks, s); break;
+    case 1: e = run_ln_bwd_dx<T, 1>(g, x, stats, gamma, resid, dx, rows, h, s); break;
+    case 2: e = run_ln_bwd_dx<T, 2>(g, x, stats, gamma, resid, dx, rows, h, s); break;
+    case 3: e = run_ln_bwd_dx<T, 3>(g, x, stats, gamma, resid, dx, rows, h, s); break;
+    case 4: e = run_ln_bwd_dx<T, 4>(g, x, stats, gamma, resid, dx, rows, h, s); break;
+    case 5: e = run_ln_bwd_dx<T, 5>(g, x, stats, gamma, resid, dx, rows, h, s); break;
+    case 6: e = run_ln_bwd_dx<T, 6>(g, x, stats, gamma, resid, dx, rows, h, s); break;
+    default: e = run_ln_bwd_dx<T, 8>(g, x, stats, gamma, resid, dx, rows, h, s); break;
   }
   if (e != hipSuccess) return e;
-  layernorm_bwd_reduce_kernel<<<(h + 63) / 64, 256, 0, s>>>(partials, dgamma, dbeta, blocks, h);
+  // gamma / beta gradients: row slices of at least 16 rows, at most kLnBwdSlices of them
+  int slices = (rows + 15) / 16;
+  if (slices > kLnBwdSlices) slices = kLnBwdSlices;
+  const int rows_per_slice = (rows + slices - 1) / slices;
+  layernorm_bwd_param_kernel<T><<<dim3((h + 127) / 128, slices), kThreads, 0, s>>>(g, x, stats, partials, rows, h,
+                                                                                  rows_per_slice);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  layernorm_bwd_reduce_kernel<<<(h + 63) / 64, 256, 0, s>>>(partials, dgamma, dbeta, slices, h);
   return hipGetLastError();
 }
 

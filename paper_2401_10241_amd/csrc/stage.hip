@@ -40,11 +40,12 @@ struct LayerOff {  // byte offsets inside one slot of each pool
 
 enum KClass {
   KC_GEMM_FWD = 0, KC_GEMM_DGRAD, KC_GEMM_WGRAD, KC_ATTN_FWD, KC_ATTN_BWD, KC_LN_FWD, KC_LN_BWD, KC_COLSUM,
-  KC_FILL, KC_SUMSQ, KC_ADAMW_STEP, KC_ADAMW_ROLLBACK, KC_TRANSPOSE, KC_COUNT
+  KC_FILL, KC_SUMSQ, KC_ADAMW_STEP, KC_ADAMW_ROLLBACK, KC_ADAMW_RESTEP, KC_TRANSPOSE, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd", "layernorm_bwd",
-    "bias_grad_colsum", "grad_zero_fill", "grad_sumsq", "adamw_step", "adamw_rollback", "weight_transpose"};
+    "bias_grad_colsum", "grad_zero_fill", "grad_sumsq", "adamw_step", "adamw_rollback", "adamw_restep",
+    "weight_transpose"};
 
 struct ProfRec {
   int cls;
@@ -230,7 +231,7 @@ size_t layout(zb_stage* st, void* arena) {
   st->tmp = bp.take<char>(T * h * E);
   st->dvec = bp.take<float>((size_t)st->b * st->a * st->s * sizeof(float));
   {  // LayerNorm-backward partials; the bias-gradient column sums reuse it for their row slices
-    size_t need = (size_t)kLnBwdBlocks * 2 * h;
+    size_t need = (size_t)kLnBwdSlices * 2 * h;
     const size_t widest = f > 3 * h ? f : 3 * h;
     if ((size_t)kColsumSlices * widest > need) need = (size_t)kColsumSlices * widest;
     st->ln_partials = bp.take<float>(need * sizeof(float));
@@ -746,7 +747,7 @@ zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, z
   }
   ZB_HIP(st, launch_decide_after_rollback(st->opt, st->hp, s));
   {
-    ProfScope ps(st, KC_ADAMW_STEP, 0, step_bytes);
+    ProfScope ps(st, KC_ADAMW_RESTEP, 0, step_bytes);
     ZB_HIP(st, launch_adamw_step(st->theta, st->adam_m, st->adam_v, st->grad, st->j_theta, st->j_m, st->j_v,
                                  st->theta16, n, st->hp, st->opt, s));
   }

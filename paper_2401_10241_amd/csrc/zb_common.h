@@ -100,13 +100,13 @@ template <typename T> hipError_t launch_attention_bwd(const AttnArgs& a, hipStre
 template <typename T>
 hipError_t launch_layernorm_fwd(const T* x, const float* gamma, const float* beta, T* out, float* stats,
                                 int rows, int h, float eps, hipStream_t s);
-// dx = resid + LNbwd(g); partial dgamma/dbeta go to `partials` ([blocks][2][h]) and are then
-// added to dgamma/dbeta in a fixed order.  Returns the number of partial blocks via launch.
+// dx = resid + LNbwd(g); partial dgamma/dbeta of up to kLnBwdSlices row slices go to `partials`
+// ([slices][2][h]) and are then added to dgamma/dbeta in slice order.
 template <typename T>
 hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid,
                                 T* dx, float* dgamma, float* dbeta, float* partials, int rows, int h,
                                 hipStream_t s);
-constexpr int kLnBwdBlocks = 128;
+constexpr int kLnBwdSlices = 16;
 
 // bias gradient: db[n] += sum_rows dy[r, n]; scratch holds kColsumSlices * n floats
 constexpr int kColsumSlices = 8;
