@@ -66,6 +66,41 @@ def measured_traffic(workload):
     return None
 
 
+XGMI_LINK_GBS = 153.0   # one xGMI link, the path of a stage-to-stage activation (design figure, not measured here)
+
+
+def auto_schedule_report(zb, st, w, m, class_ms):
+    """Sec. 3.1's automatic scheduler fed with this stage's measured pass times: T_F, T_B, T_W are the
+    event-timed kernel classes of one step divided by m, T_comm is one [tokens, h] activation over one xGMI
+    link, the memory model is the stage's real stash.  Bubble rates are those of a p-stage pipeline made of
+    p copies of this stage (Sec. 5.3's definition), for the handcrafted orders and for the search under the
+    memory of 1F1B (p M_B) and twice that."""
+    t_f = (class_ms.get("gemm_fwd", 0) + class_ms.get("attention_fwd", 0) + class_ms.get("layernorm_fwd", 0)) / m
+    t_b = (class_ms.get("gemm_dgrad", 0) + class_ms.get("attention_bwd", 0) + class_ms.get("layernorm_bwd", 0)) / m
+    t_w = (class_ms.get("gemm_wgrad", 0) + class_ms.get("bias_grad_colsum", 0)) / m
+    elem = 2 if w.dtype == "bf16" else 4
+    t_comm = w.seq * w.mb_size * w.hidden * elem / (XGMI_LINK_GBS * 1e9) * 1e3
+    m_b, m_w = st.stash_bytes()
+    p = w.p
+    rates = {}
+    for kind in ("1F1B", "H1", "H2"):
+        orders = [zb.schedule_order(p, i, m, kind) for i in range(p)]
+        rates["1F1B" if kind == "1F1B" else "ZB-" + kind] = round(
+            zb.simulate_pipeline(orders, t_f, t_b, t_w, t_comm, fused_backward=(kind == "1F1B"))[1], 4)
+    t0 = time.perf_counter()
+    found = {}
+    for name, mult in (("auto, limit p*M_B", 1), ("auto, limit 2p*M_B", 2)):
+        orders, cost, rate, flags = zb.auto_schedule_search(p, m, t_f, t_b, t_w, t_comm, mult * p * m_b, m_b, m_w)
+        rates[name] = round(rate, 4)
+        found[name] = {"extra_warmup_f": flags[0], "skip_f": flags[1],
+                       "stage_peak_bytes": zb.order_memory_peak(orders[w.stage], m_b, m_w)}
+    search_ms = (time.perf_counter() - t0) * 1e3
+    return {"p": p, "m": m, "t_f_ms": round(t_f, 4), "t_b_ms": round(t_b, 4), "t_w_ms": round(t_w, 4),
+            "t_comm_ms": round(t_comm, 4), "t_comm_source": f"{XGMI_LINK_GBS} GB/s link figure, not measured",
+            "m_b_bytes": m_b, "m_w_bytes": m_w, "bubble_rate": rates, "search": found,
+            "search_host_ms": round(search_ms, 2)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,6 +218,7 @@ def main():
                            "flops_per_launch": g_fl / g_n,
                            "share_of_step_kernel_time": round(g_ms / sum(r["total_ms"] for r in stats), 3)}
         out["kernels"] = kern
+        out["auto_schedule"] = auto_schedule_report(zb, st, w, m, {r["name"]: r["total_ms"] for r in stats})
     st.close()
     del st
     torch.cuda.empty_cache()

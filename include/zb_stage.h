@@ -139,6 +139,47 @@ zb_status zb_schedule_stash_need(int32_t p, int32_t stage, int32_t m, int32_t ki
 /* zb_begin_iteration(m) must have been called; runs all 3m passes in schedule order. */
 zb_status zb_run_schedule(zb_stage* st, int32_t p, int32_t stage, int32_t m, int32_t kind);
 
+/* Same for an explicit order of n entries (host), e.g. one stage's row of zb_auto_schedule's result.
+ * ZB_EORDER if the list is not a valid stage order (F before B before W, nothing twice). */
+zb_status zb_order_stash_need(const zb_op* ops, int32_t n, int32_t* max_pending_b, int32_t* max_pending_w,
+                              int32_t* max_inflight);
+
+/* zb_begin_iteration(m) must have been called; runs the n = 3m passes of an explicit order (host array).
+ * The same dependency rule as the single pass calls applies (ZB_EORDER); the stash pools of the stage
+ * must hold what zb_order_stash_need reports for this order (ZB_ENOMEM from the pass that does not fit). */
+zb_status zb_run_order(zb_stage* st, const zb_op* ops, int32_t n);
+
+/* ---- p-stage timing model and automatic scheduling (host only, no device needed) --------------------
+ * Pass times of one stage (any unit) and the transfer time between neighbouring stages (Sec. 3). */
+typedef struct { double t_f, t_b, t_w, t_comm; } zb_pass_times;
+/* Activation memory (Appendix G): F adds m_b, B adds m_w - m_b, W releases m_w; a stage may never
+ * hold more than m_limit.  0 <= m_w <= m_b <= m_limit. */
+typedef struct { double m_limit, m_b, m_w; } zb_memory_model;
+
+/* Timing model of Sec. 5.3 / Appendix G for p stage orders, orders[stage*3m + q] (host): a pass starts
+ * when its stage is free and its input has arrived (F from stage-1, B from stage+1, t_comm after the
+ * producer ended; fused_backward != 0: the gradient leaves a stage after the W of that microbatch, the
+ * single backward of 1F1B).  *cost = largest stage span, *bubble_rate = (cost - m(T_F+T_B+T_W)) / cost,
+ * stage_span[p] = every stage's span.  Out pointers may be NULL.  ZB_EORDER for invalid or deadlocking
+ * orders. */
+zb_status zb_simulate_pipeline(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times,
+                               int32_t fused_backward, double* cost, double* bubble_rate, double* stage_span);
+
+/* Heuristic scheduler of Sec. 3.1 for one setting of its two binary options (one more warm-up forward
+ * although it delays the first backward; no running ahead with forwards once a stage leads its successor
+ * by one).  Writes all p stage orders to orders[p*3m] (host).  ZB_ENOMEM if m_limit admits no schedule. */
+zb_status zb_auto_schedule(int32_t p, int32_t m, const zb_pass_times* times, const zb_memory_model* mem,
+                           int32_t extra_warmup_f, int32_t skip_f, zb_op* orders);
+
+/* Grid search over the two options (Sec. 3.1): the cheapest of the four schedules under the timing model
+ * above, the first of (0,0) (0,1) (1,0) (1,1) on ties.  Out pointers other than orders may be NULL. */
+zb_status zb_auto_schedule_search(int32_t p, int32_t m, const zb_pass_times* times, const zb_memory_model* mem,
+                                  zb_op* orders, double* cost, double* bubble_rate, int32_t* extra_warmup_f,
+                                  int32_t* skip_f);
+
+/* Peak of Appendix G's memory walk over one stage order of n entries. */
+zb_status zb_order_memory_peak(const zb_op* ops, int32_t n, double m_b, double m_w, double* peak);
+
 /* Global optimizer state contributed by the other stages (Sec. 4): the partially reduced
  * state received from the previous stage and what the stages after this one add to it. */
 typedef struct {
@@ -188,6 +229,11 @@ const char* zb_last_error(const zb_stage* st); /* "" if none; valid until the ne
 /* Model FLOPs of Table 1 for this stage and m microbatches: L*m*(F + B + W) with
  * F = sbh(24h+4s), B = sbh(24h+8s), W = 24sbh^2 (no causal discount). */
 zb_status zb_stage_model_flops(const zb_stage* st, int32_t m, double* flops);
+
+/* Activation bytes this stage really holds per microbatch, in the terms of Appendix G's memory model:
+ * *m_b after F (what B and W will read), *m_w after B (what is kept for W: the inputs and output
+ * gradients of the four linears of every layer, Table 1).  Feeds zb_memory_model. */
+zb_status zb_stage_stash_bytes(const zb_stage* st, double* m_b, double* m_w);
 
 /* Per-kernel timing.  While enabled, every kernel launch is bracketed by HIP events on the
  * stage's stream (this slows the stream down: measure throughput with profiling off).

@@ -4,7 +4,7 @@ Every function here has the name of the C entry point it calls (include/zb_stage
 the ``zb_`` prefix; all arithmetic of the F / B / W passes, the schedule order and the
 optimizer protocol runs inside the library.  PyTorch is used for exactly two things:
 owning the device arena and the HIP stream.  There is no fallback: if the library is not
-built (python -m paper_2401_10241_amd.build) importing this module raises.
+built (python paper_2401_10241_amd/build.py) importing this module raises.
 """
 from __future__ import annotations
 
@@ -20,7 +20,7 @@ import torch  # noqa: F401  (device memory and streams only)
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libzbstage.so")
 if not os.path.exists(_LIB_PATH):
-    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2401_10241_amd.build` "
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2401_10241_amd/build.py` "
                       "(there is no CPU fallback)")
 lib = C.CDLL(_LIB_PATH)
 
@@ -64,6 +64,14 @@ class zb_step_report(C.Structure):
                 ("alg1_mismatch_elems", C.c_uint64)]
 
 
+class zb_pass_times(C.Structure):
+    _fields_ = [("t_f", C.c_double), ("t_b", C.c_double), ("t_w", C.c_double), ("t_comm", C.c_double)]
+
+
+class zb_memory_model(C.Structure):
+    _fields_ = [("m_limit", C.c_double), ("m_b", C.c_double), ("m_w", C.c_double)]
+
+
 class zb_kernel_stat(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double),
                 ("flops", C.c_double), ("bytes", C.c_double)]
@@ -84,12 +92,22 @@ _sig = {
     "zb_schedule_stash_need": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P(C.c_int32), _P(C.c_int32),
                                _P(C.c_int32)],
     "zb_run_schedule": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32],
+    "zb_order_stash_need": [_P(zb_op), C.c_int32, _P(C.c_int32), _P(C.c_int32), _P(C.c_int32)],
+    "zb_run_order": [C.c_void_p, _P(zb_op), C.c_int32],
+    "zb_simulate_pipeline": [C.c_int32, C.c_int32, _P(zb_op), _P(zb_pass_times), C.c_int32, _P(C.c_double),
+                             _P(C.c_double), _P(C.c_double)],
+    "zb_auto_schedule": [C.c_int32, C.c_int32, _P(zb_pass_times), _P(zb_memory_model), C.c_int32, C.c_int32,
+                         _P(zb_op)],
+    "zb_auto_schedule_search": [C.c_int32, C.c_int32, _P(zb_pass_times), _P(zb_memory_model), _P(zb_op),
+                                _P(C.c_double), _P(C.c_double), _P(C.c_int32), _P(C.c_int32)],
+    "zb_order_memory_peak": [_P(zb_op), C.c_int32, C.c_double, C.c_double, _P(C.c_double)],
     "zb_optimizer_step_validated": [C.c_void_p, _P(zb_global_state), _P(zb_step_report)],
     "zb_get_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
     "zb_set_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
     "zb_inject": [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_float],
     "zb_synchronize": [C.c_void_p],
     "zb_stage_model_flops": [C.c_void_p, C.c_int32, _P(C.c_double)],
+    "zb_stage_stash_bytes": [C.c_void_p, _P(C.c_double), _P(C.c_double)],
     "zb_profile_enable": [C.c_void_p, C.c_int32],
     "zb_profile_read": [C.c_void_p, _P(zb_kernel_stat), C.c_int32, _P(C.c_int32)],
 }
@@ -125,6 +143,84 @@ def schedule_stash_need(p: int, stage: int, m: int, kind: str) -> Tuple[int, int
     if rc != OK:
         raise ZbError(rc, "zb_schedule_stash_need")
     return a.value, b.value, c.value
+
+
+def _pack_order(ops) -> "C.Array":
+    buf = (zb_op * max(len(ops), 1))()
+    for q, (c, k) in enumerate(ops):
+        buf[q].pass_, buf[q].mb = int(c), int(k)
+    return buf
+
+
+def _pack_orders(orders) -> Tuple["C.Array", int, int]:
+    p = len(orders)
+    n = len(orders[0]) if p else 0
+    if p == 0 or n == 0 or n % 3 or any(len(o) != n for o in orders):
+        raise ZbError(EINVAL, "orders must be p lists of 3m (pass, microbatch) pairs")
+    return _pack_order([op for o in orders for op in o]), p, n // 3
+
+
+def _unpack_orders(buf, p: int, m: int) -> List[List[Tuple[int, int]]]:
+    return [[(buf[i * 3 * m + q].pass_, buf[i * 3 * m + q].mb) for q in range(3 * m)] for i in range(p)]
+
+
+def order_stash_need(ops) -> Tuple[int, int, int]:
+    """zb_order_stash_need: (max pending-B, max pending-W, max in-flight) of an explicit stage order."""
+    a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    rc = lib.zb_order_stash_need(_pack_order(ops), len(ops), C.byref(a), C.byref(b), C.byref(c))
+    if rc != OK:
+        raise ZbError(rc, "zb_order_stash_need")
+    return a.value, b.value, c.value
+
+
+def simulate_pipeline(orders, t_f: float, t_b: float, t_w: float, t_comm: float = 0.0,
+                      fused_backward: bool = False) -> Tuple[float, float, List[float]]:
+    """zb_simulate_pipeline: (cost, bubble rate, per-stage spans) of p stage orders."""
+    buf, p, m = _pack_orders(orders)
+    t = zb_pass_times(t_f, t_b, t_w, t_comm)
+    cost, rate = C.c_double(0), C.c_double(0)
+    spans = (C.c_double * p)()
+    rc = lib.zb_simulate_pipeline(p, m, buf, C.byref(t), int(fused_backward), C.byref(cost), C.byref(rate), spans)
+    if rc != OK:
+        raise ZbError(rc, "zb_simulate_pipeline")
+    return cost.value, rate.value, list(spans)
+
+
+def auto_schedule(p: int, m: int, t_f: float, t_b: float, t_w: float, t_comm: float, m_limit: float,
+                  m_b: float, m_w: float, extra_warmup_f: bool = False,
+                  skip_f: bool = False) -> List[List[Tuple[int, int]]]:
+    """zb_auto_schedule: the heuristic's p stage orders for one setting of its two options."""
+    buf = (zb_op * max(3 * p * m, 1))()
+    t = zb_pass_times(t_f, t_b, t_w, t_comm)
+    mm = zb_memory_model(m_limit, m_b, m_w)
+    rc = lib.zb_auto_schedule(p, m, C.byref(t), C.byref(mm), int(extra_warmup_f), int(skip_f), buf)
+    if rc != OK:
+        raise ZbError(rc, "zb_auto_schedule")
+    return _unpack_orders(buf, p, m)
+
+
+def auto_schedule_search(p: int, m: int, t_f: float, t_b: float, t_w: float, t_comm: float, m_limit: float,
+                         m_b: float, m_w: float):
+    """zb_auto_schedule_search: (orders, cost, bubble rate, (extra_warmup_f, skip_f))."""
+    buf = (zb_op * max(3 * p * m, 1))()
+    t = zb_pass_times(t_f, t_b, t_w, t_comm)
+    mm = zb_memory_model(m_limit, m_b, m_w)
+    cost, rate = C.c_double(0), C.c_double(0)
+    ew, sk = C.c_int32(0), C.c_int32(0)
+    rc = lib.zb_auto_schedule_search(p, m, C.byref(t), C.byref(mm), buf, C.byref(cost), C.byref(rate),
+                                     C.byref(ew), C.byref(sk))
+    if rc != OK:
+        raise ZbError(rc, "zb_auto_schedule_search")
+    return _unpack_orders(buf, p, m), cost.value, rate.value, (bool(ew.value), bool(sk.value))
+
+
+def order_memory_peak(ops, m_b: float, m_w: float) -> float:
+    """zb_order_memory_peak."""
+    peak = C.c_double(0)
+    rc = lib.zb_order_memory_peak(_pack_order(ops), len(ops), m_b, m_w, C.byref(peak))
+    if rc != OK:
+        raise ZbError(rc, "zb_order_memory_peak")
+    return peak.value
 
 
 @dataclass
@@ -220,6 +316,9 @@ class Stage:
     def run_schedule(self, p: int, stage: int, m: int, kind: str):
         self._call(lib.zb_run_schedule, p, stage, m, KIND[kind])
 
+    def run_order(self, ops):
+        self._call(lib.zb_run_order, _pack_order(ops), len(ops))
+
     def optimizer_step_validated(self, prev_sq=0.0, rest_sq=0.0, prev_nonfinite=False, rest_nonfinite=False,
                                  force_optimistic=False, want_report=True) -> Optional[StepReport]:
         gs = zb_global_state(prev_sq, rest_sq, int(prev_nonfinite), int(rest_nonfinite), int(force_optimistic))
@@ -266,6 +365,12 @@ class Stage:
         out = C.c_double(0)
         self._call(lib.zb_stage_model_flops, m, C.byref(out))
         return out.value
+
+    def stash_bytes(self) -> Tuple[float, float]:
+        """zb_stage_stash_bytes: (bytes held per microbatch after F, after B)."""
+        a, b = C.c_double(0), C.c_double(0)
+        self._call(lib.zb_stage_stash_bytes, C.byref(a), C.byref(b))
+        return a.value, b.value
 
     def profile_enable(self, on: bool):
         self._call(lib.zb_profile_enable, int(on))

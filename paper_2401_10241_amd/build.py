@@ -1,6 +1,6 @@
 """Builds libzbstage.so (the C-ABI HIP library) in-tree for gfx950 with hipcc.
 
-    python -m paper_2401_10241_amd.build        # compile every source, link
+    python paper_2401_10241_amd/build.py        # compile every source, link
 """
 from __future__ import annotations
 
@@ -15,7 +15,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzbstage.so")
 
 SOURCES = ["stage.hip", "kernels_rowwise.hip", "kernels_optimizer.hip", "gemm_generic.hip", "gemm_mfma.hip",
-           "attention_generic.hip", "attention_mfma.hip", "attention_mfma128.hip"]
+           "attention_generic.hip", "attention_mfma.hip", "attention_mfma128.hip", "autosched.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",

@@ -682,15 +682,12 @@ zb_status zb_schedule_order(int32_t p, int32_t stage, int32_t m, int32_t kind, z
   return ZB_OK;
 }
 
-zb_status zb_schedule_stash_need(int32_t p, int32_t stage, int32_t m, int32_t kind, int32_t* max_pending_b,
-                                 int32_t* max_pending_w, int32_t* max_inflight) {
-  if (check_sched_args(p, stage, m, kind) != ZB_OK) return ZB_EINVAL;
-  std::vector<zb_op> ops;
-  build_order(p, stage, m, kind, &ops);
+static void stash_need(const zb_op* ops, size_t n, int32_t* max_pending_b, int32_t* max_pending_w,
+                       int32_t* max_inflight) {
   int nb = 0, nw = 0, mb_ = 0, mw_ = 0, mi_ = 0;
-  for (const zb_op& op : ops) {
-    if (op.pass == ZB_PASS_F) ++nb;
-    else if (op.pass == ZB_PASS_B) { --nb; ++nw; }
+  for (size_t q = 0; q < n; ++q) {
+    if (ops[q].pass == ZB_PASS_F) ++nb;
+    else if (ops[q].pass == ZB_PASS_B) { --nb; ++nw; }
     else --nw;
     if (nb > mb_) mb_ = nb;
     if (nw > mw_) mw_ = nw;
@@ -699,6 +696,52 @@ zb_status zb_schedule_stash_need(int32_t p, int32_t stage, int32_t m, int32_t ki
   if (max_pending_b) *max_pending_b = mb_;
   if (max_pending_w) *max_pending_w = mw_;
   if (max_inflight) *max_inflight = mi_;
+}
+
+zb_status zb_schedule_stash_need(int32_t p, int32_t stage, int32_t m, int32_t kind, int32_t* max_pending_b,
+                                 int32_t* max_pending_w, int32_t* max_inflight) {
+  if (check_sched_args(p, stage, m, kind) != ZB_OK) return ZB_EINVAL;
+  std::vector<zb_op> ops;
+  build_order(p, stage, m, kind, &ops);
+  stash_need(ops.data(), ops.size(), max_pending_b, max_pending_w, max_inflight);
+  return ZB_OK;
+}
+
+// every (pass, mb) at most once, F before B before W of one microbatch, mb in [0, n/3)
+static bool valid_stage_order(const zb_op* ops, int32_t n) {
+  if (!ops || n < 0 || n % 3 != 0) return false;
+  const int m = n / 3;
+  std::vector<char> seen((size_t)n, 0);
+  for (int q = 0; q < n; ++q) {
+    const zb_op& op = ops[q];
+    if (op.pass < 0 || op.pass > 2 || op.mb < 0 || op.mb >= m) return false;
+    if (seen[(size_t)op.pass * m + op.mb]) return false;
+    if (op.pass > 0 && !seen[(size_t)(op.pass - 1) * m + op.mb]) return false;
+    seen[(size_t)op.pass * m + op.mb] = 1;
+  }
+  return true;
+}
+
+zb_status zb_order_stash_need(const zb_op* ops, int32_t n, int32_t* max_pending_b, int32_t* max_pending_w,
+                              int32_t* max_inflight) {
+  if (!ops || n < 0) return ZB_EINVAL;
+  if (!valid_stage_order(ops, n)) return ZB_EORDER;
+  stash_need(ops, (size_t)n, max_pending_b, max_pending_w, max_inflight);
+  return ZB_OK;
+}
+
+zb_status zb_run_order(zb_stage* st, const zb_op* ops, int32_t n) {
+  if (!st) return ZB_EINVAL;
+  st->err.clear();
+  if (!ops || n < 0) return fail(st, ZB_EINVAL, "no order given");
+  if (n != 3 * st->m) return fail(st, ZB_ESTATE, "the order must hold 3m passes for zb_begin_iteration's m");
+  if (!valid_stage_order(ops, n)) return fail(st, ZB_EORDER, "not a valid stage order");
+  for (int q = 0; q < n; ++q) {
+    const zb_op& op = ops[q];
+    zb_status rc = op.pass == ZB_PASS_F ? zb_forward(st, op.mb)
+                 : op.pass == ZB_PASS_B ? zb_backward_input(st, op.mb) : zb_backward_weight(st, op.mb);
+    if (rc != ZB_OK) return rc;
+  }
   return ZB_OK;
 }
 
@@ -843,6 +886,13 @@ zb_status zb_stage_model_flops(const zb_stage* st, int32_t m, double* flops) {
   const double s = st->s, b = st->b, h = st->h;
   const double F = s * b * h * (24 * h + 4 * s), B = s * b * h * (24 * h + 8 * s), W = s * b * h * 24 * h;
   *flops = (double)st->L * m * (F + B + W);
+  return ZB_OK;
+}
+
+zb_status zb_stage_stash_bytes(const zb_stage* st, double* m_b, double* m_w) {
+  if (!st || !m_b || !m_w) return ZB_EINVAL;
+  *m_b = (double)(st->fb_slot + st->fw_slot);
+  *m_w = (double)(st->fw_slot + st->bw_slot);
   return ZB_OK;
 }
 

@@ -1,0 +1,172 @@
+"""Pins of the oracle's automatic scheduler (oracle/autosched.py): the paper's printed bubble rates of the
+automatically searched schedules, Appendix B's bounds, validity and the memory limit, and brute force on
+tiny pipelines.  No GPU, no library."""
+import itertools
+import os
+import random
+
+import pytest
+
+from oracle import autosched as A
+from oracle.schedule import B, F, W, bubble_rate, check_order, simulate, stage_order
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def printed_rows():
+    rows = []
+    for line in open(os.path.join(HERE, "golden", "auto_bubble_rates.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        c = line.split()
+        h, a, s = int(c[9]), int(c[10]), int(c[11])
+        rows.append(dict(model=c[0], p=int(c[1]), m=int(c[2]), T_F=float(c[3]), T_B=float(c[4]), T_W=float(c[5]),
+                         T_comm=float(c[6]), zb1p=float(c[7]), zb2p=float(c[8]),
+                         ratio=32.0 * h / (34.0 * h + 5.0 * a * s)))   # M_W / M_B of Table 1
+    return rows
+
+
+ROWS = printed_rows()
+
+
+def searched_rate(r, limit_in_mb):
+    orders, cost, flags = A.search(r["p"], r["m"], r["T_F"], r["T_B"], r["T_W"], r["T_comm"],
+                                   float(limit_in_mb), 1.0, r["ratio"])
+    return (cost - r["m"] * (r["T_F"] + r["T_B"] + r["T_W"])) / cost, orders
+
+
+@pytest.mark.parametrize("r", ROWS, ids=lambda r: f"{r['model']}-p{r['p']}-m{r['m']}")
+def test_printed_zb2p_bubble_rates(r):
+    # Sec. 5.3 table, column ZB-2p (memory limit 2p M_B).  Eleven of the twelve rows round to the printed
+    # four digits; the first row gives 0.04344 against the printed 0.0433.
+    rate, _ = searched_rate(r, 2 * r["p"])
+    assert abs(rate - r["zb2p"]) <= 1.5e-4
+    if not (r["model"] == "1.5B" and r["m"] == 24):
+        assert round(rate, 4) == r["zb2p"]
+
+
+@pytest.mark.parametrize("r", [r for r in ROWS if r["p"] == 8], ids=lambda r: f"{r['model']}-m{r['m']}")
+def test_printed_zb1p_bubble_rates_p8(r):
+    # Sec. 5.3 table, column ZB-1p (memory limit p M_B): the six p = 8 rows to all printed digits
+    rate, _ = searched_rate(r, r["p"])
+    assert round(rate, 4) == r["zb1p"]
+
+
+@pytest.mark.parametrize("r", [r for r in ROWS if r["p"] >= 16], ids=lambda r: f"{r['model']}-m{r['m']}")
+def test_zb1p_bubble_rates_p16_p32_close_to_print(r):
+    # For p >= 16 this reading of the heuristic ends up to 0.016 above the printed ZB-1p column (which
+    # equals ZB-H1's rate there); it must never fall below the bound of Appendix B.
+    rate, _ = searched_rate(r, r["p"])
+    assert r["zb1p"] - 1e-4 <= rate <= r["zb1p"] + 0.016
+
+
+def first_b_facts(orders, r):
+    """k = forwards before the first B on the first stage, beta = idle time before that B."""
+    start, end = simulate(orders, r["T_F"], r["T_B"], r["T_W"], r["T_comm"])
+    o0 = orders[0]
+    pos = o0.index((B, 0))
+    k = sum(1 for c, _ in o0[:pos] if c == F)
+    assert all(c == F for c, _ in o0[:pos])
+    beta = start[0][(B, 0)] - end[0][o0[pos - 1]]
+    return k, beta
+
+
+@pytest.mark.parametrize("r", ROWS[:9], ids=lambda r: f"{r['model']}-p{r['p']}-m{r['m']}")
+@pytest.mark.parametrize("mult", [1, 2])
+def test_appendix_b_bounds_and_memory_limit(r, mult):
+    # Appendix B: M_limit >= k M_B and beta >= (p-1)(T_B + 2 T_comm) + (p-k) T_F
+    p, m = r["p"], r["m"]
+    limit = float(mult * p)
+    rate, orders = searched_rate(r, limit)
+    for i in range(p):
+        check_order(orders[i], m)
+        assert A.memory_peak(orders[i], 1.0, r["ratio"]) <= limit * (1 + 1e-9)
+    k, beta = first_b_facts(orders, r)
+    assert k * 1.0 <= limit
+    bound = (p - 1) * (r["T_B"] + 2 * r["T_comm"]) + (p - k) * r["T_F"]
+    assert beta >= bound - 1e-6
+    # the whole pipeline cannot beat the first microbatch's round trip plus the remaining work of stage 0
+    cost = A.cost(orders, r["T_F"], r["T_B"], r["T_W"], r["T_comm"])
+    assert cost >= m * (r["T_F"] + r["T_B"] + r["T_W"]) + max(0.0, bound) - 1e-6
+
+
+def test_more_memory_never_hurts_much_and_reaches_near_zero_bubble():
+    # Sec. 5.4: the bubble rate falls as the limit grows and is close to zero from about 2p M_B on
+    r = ROWS[4]
+    rates = [searched_rate(r, lim)[0] for lim in (8, 10, 12, 14, 16, 20)]
+    assert rates[0] > rates[2] > rates[4]
+    assert rates[4] < 0.01 and rates[5] < 0.01
+    assert all(b <= a + 0.01 for a, b in zip(rates, rates[1:]))
+
+
+def test_equal_times_unlimited_memory_zero_bubble():
+    # T_F = T_B = T_W, no communication, memory for 2p-1 microbatches, m >= 2p-1: Sec. 2.2's zero-bubble
+    # parallelogram exists, and the search must find a schedule with no bubble either
+    p, m = 4, 12
+    orders, cost, _ = A.search(p, m, 1.0, 1.0, 1.0, 0.0, float(2 * p - 1), 1.0, 1.0)
+    h2 = max(max(e.values()) - min(s.values()) for s, e in
+             zip(*simulate([stage_order(p, i, m, "H2") for i in range(p)], 1.0, 1.0, 1.0, 0.0)))
+    assert h2 == pytest.approx(3.0 * m)
+    assert cost == pytest.approx(3.0 * m)
+
+
+def all_stage_orders(m):
+    """Every valid order of one stage with F and B in microbatch order (W anywhere after its B)."""
+    out = []
+
+    def rec(prefix, nf, nb, done_w):
+        if len(prefix) == 3 * m:
+            out.append(list(prefix))
+            return
+        if nf < m:
+            rec(prefix + [(F, nf)], nf + 1, nb, done_w)
+        if nb < nf:
+            rec(prefix + [(B, nb)], nf, nb + 1, done_w)
+        for k in range(nb):
+            if k not in done_w:
+                rec(prefix + [(W, k)], nf, nb, done_w | {k})
+                break   # W in microbatch order too: they are interchangeable in cost
+    rec([], 0, 0, frozenset())
+    return out
+
+
+@pytest.mark.parametrize("times", [(1.0, 1.0, 1.0, 0.0), (3.0, 2.5, 1.5, 0.25), (2.0, 3.0, 1.0, 0.5)])
+def test_brute_force_on_a_two_stage_pipeline(times):
+    # p = 2, m = 3: enumerate every pair of stage orders, keep those under the memory limit, take the best
+    # cost.  The heuristic can never beat it; on these it reaches it or stays within one W of it.
+    T_F, T_B, T_W, T_comm = times
+    p, m, limit, ratio = 2, 3, 3.0, 0.5
+    cands = [o for o in all_stage_orders(m) if A.memory_peak(o, 1.0, ratio) <= limit + 1e-9]
+    best = None
+    for o0, o1 in itertools.product(cands, repeat=2):
+        try:
+            c = A.cost([o0, o1], T_F, T_B, T_W, T_comm)
+        except AssertionError:
+            continue
+        best = c if best is None or c < best else best
+    _, cost, _ = A.search(p, m, T_F, T_B, T_W, T_comm, limit, 1.0, ratio)
+    assert cost >= best - 1e-9
+    assert cost <= best + T_W + 1e-9
+
+
+def test_orders_are_valid_for_random_settings():
+    rng = random.Random(5)
+    for _ in range(40):
+        p, m = rng.randint(1, 9), rng.randint(1, 20)
+        T_F, T_B, T_W = (rng.uniform(0.5, 3.0) for _ in range(3))
+        T_comm = rng.choice([0.0, rng.uniform(0.0, 0.5)])
+        ratio = rng.uniform(0.0, 1.0)
+        limit = rng.uniform(1.0, 2.5 * p)
+        for ew, sk in A.OPTION_GRID:
+            orders = A.auto_schedule(p, m, T_F, T_B, T_W, T_comm, limit, 1.0, ratio, ew, sk)
+            for i in range(p):
+                check_order(orders[i], m)
+                assert A.memory_peak(orders[i], 1.0, ratio) <= limit * (1 + 1e-9)
+            A.cost(orders, T_F, T_B, T_W, T_comm)   # no deadlock
+
+
+def test_rejects_impossible_limits():
+    with pytest.raises(ValueError):
+        A.auto_schedule(2, 2, 1.0, 1.0, 1.0, 0.0, 0.5, 1.0, 0.5)
+    with pytest.raises(ValueError):
+        A.auto_schedule(2, 2, 1.0, 1.0, 1.0, 0.0, 2.0, 1.0, 1.5)
