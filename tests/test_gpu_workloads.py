@@ -198,3 +198,25 @@ def test_c5_full_shapes_rollback_identity():
             assert after[0].tobytes() != before[0].tobytes()
     assert rep.t == 2
     dev.close()
+
+
+@pytest.mark.parametrize("name,h,a,ffn,b", [("1.5B-b6", 2304, 24, 9216, 6), ("6.2B-b3", 4096, 32, 16384, 3)])
+def test_papers_microbatch_sizes(name, h, a, ffn, b):
+    # Sec. 5.1's table runs the 1.5B model with 6 and the 6.2B model with 3 sequences per microbatch
+    # (BASELINE's c2 / c3 use 1): one layer, two microbatches of that size, every tensor against the oracle
+    from zb_testlib import compare_outputs, load_iteration
+    w = zb_inputs.Workload(name, "bf16", 1, h, a, ffn, 1024, b, 8, 4, 2, "H1", seed=41)
+    params = zb_inputs.stage_params(w)
+    dev = make_device_stage(w, w.m)
+    orc = make_oracle(w, params)
+    dev.set_params(params)
+    dev.begin_iteration(0, w.m)
+    orc.begin_iteration(w.m)
+    load_iteration(w, 0, w.m, dev, orc)
+    dev.run_schedule(w.p, w.stage, w.m, w.kind)
+    dev.synchronize()
+    orc.run(stage_order(w.p, w.stage, w.m, w.kind))
+    e1 = compare_outputs(dev, orc, w.m, TOL["bf16"])
+    e2 = compare_grads(dev, orc, TOL["bf16"])
+    print(f"[{name}] outputs {e1:.2e} grads {e2:.2e}", flush=True)
+    dev.close()
