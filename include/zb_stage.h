@@ -90,6 +90,8 @@ typedef struct {
   int32_t journal;          /* 1: the step keeps an undo journal so that rollback restores
                                theta, m, v bit for bit (12 B/parameter); 0: rollback is
                                Algorithm 1's arithmetic inverse only (exact to rounding) */
+  int32_t group_w;          /* 1: zb_run_schedule / zb_run_order run consecutive W passes of the order as
+                               one grouped W (zb_backward_weight_group); 0: one by one.  Same bits. */
   float ln_eps;             /* 1e-5 */
   float lr, beta1, beta2, adam_eps, weight_decay; /* Algorithm 1's gamma, beta1, beta2, eps, lambda */
   float clip;               /* global gradient-norm clipping threshold (Sec. 4) */
@@ -99,7 +101,7 @@ typedef struct {
 } zb_config;
 
 /* Fills the numeric fields of *cfg with defaults (ln_eps 1e-5, lr 1e-4, betas 0.9/0.95,
- * eps 1e-8, weight decay 0.01, clip 1.0, journal 1, dtype bf16); shapes are left 0. */
+ * eps 1e-8, weight decay 0.01, clip 1.0, journal 1, group_w 1, dtype bf16); shapes are left 0. */
 zb_status zb_config_defaults(zb_config* cfg);
 
 /* Device bytes zb_stage_init needs for this configuration (arena fields ignored). */
@@ -125,6 +127,13 @@ zb_status zb_begin_iteration(zb_stage* st, int32_t iter, int32_t m);
 zb_status zb_forward(zb_stage* st, int32_t mb);
 zb_status zb_backward_input(zb_stage* st, int32_t mb);
 zb_status zb_backward_weight(zb_stage* st, int32_t mb);
+
+/* W of n microbatches at once, mbs[0..n) (host) in that order, grouped by parameter (Appendix A groups
+ * the deferred W passes by parameter; Sec. 2: W may run anywhere after its B): every weight gradient is
+ * read once, receives the n products one after the other and is written once.  The gradients are bit for
+ * bit those of zb_backward_weight(mbs[0]), ..., zb_backward_weight(mbs[n-1]).  Each mbs[i] must have
+ * done B and not W (ZB_EORDER otherwise, nothing is run then); n >= 1. */
+zb_status zb_backward_weight_group(zb_stage* st, const int32_t* mbs, int32_t n);
 
 /* Per-stage pass order (host only; `stage` is 0-based, the paper's worker i = stage+1).
  * Writes 3m entries to out (host, capacity cap) and their number to *n. */

@@ -95,6 +95,17 @@ template <typename T> hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   bool taken = false;
   hipError_t e = launch_gemm_mfma<T>(g, s, &taken);
   if (taken) return e;
+  if (g.group >= 2) {  // no grouped kernel for this shape: the pairs one after the other
+    if (g.group > kGemmGroupMax || g.epilogue != EPI_ACCUM_F32) return hipErrorInvalidValue;
+    for (int i = 0; i < g.group; ++i) {
+      GemmArgs one = g;
+      one.group = 0;
+      one.A = g.group_a[i];
+      one.B = g.group_b[i];
+      if ((e = launch_gemm<T>(one, s)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   return launch_gemm_generic<T>(g, s);
 }
 

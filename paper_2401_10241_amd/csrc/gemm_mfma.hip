@@ -29,6 +29,7 @@
 // starting at 8 * (l >> 5); it receives column (l & 31) and rows 8*(v/4) + 4*(l >> 5) + v%4 of the
 // 32 x 32 result in accumulator element v.
 #include <type_traits>
+#include <cstdlib>
 
 #include "gemm_epilogue.h"
 #ifndef ZB_DIAG_MFMA
@@ -320,6 +321,132 @@ __global__ __launch_bounds__(256) void gemm_splitk_fixup_kernel(const float* __r
   *reinterpret_cast<bf16x4*>((bf16_t*)epi.out0 + i4) = o0;
 }
 
+// Grouped wgrad: C += A_0^T B_0, then += A_1^T B_1, ... for `ngroup` operand pairs of one shape (the W
+// passes of consecutive microbatches).  The old C is read once, when the kernel starts, and the new C is
+// written once; the ring of LDS stages runs on across the pairs without draining.  Each pair's product is
+// accumulated from zero and added to the running C in fp32, so the result has exactly the bits of
+// `ngroup` separate accumulate launches.  128 x 256 tile (64 accumulator + 64 running-C registers per lane:
+// eight wavefronts at two per SIMD have 256 registers each), one workgroup per CU, five-stage ring.
+struct GroupPtrs {
+  const bf16_t* a[kGemmGroupMax];
+  const bf16_t* b[kGemmGroupMax];
+};
+
+template <int BM, int BS>
+__global__ __launch_bounds__(512, 2) void gemm_wgrad_group_kernel(GroupPtrs gp, int ngroup, int M, int N, int Kc,
+                                                                  long lda, long ldb, float* __restrict__ outf) {
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  typedef Cfg<BM, BS, true> C;
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sB = sA + C::A_STAGES * C::A_ELEMS;
+  constexpr int WM = BM / 2;
+  constexpr int MT = WM / 32, NT = WN / 32;
+
+  const int tiles_m = M / BM, tiles_n = N / BN;
+  const int nblk = gridDim.x;
+  int pid = blockIdx.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  constexpr int GROUP_M = 8;
+  const int band = pid / (GROUP_M * tiles_n);
+  const int band_rows = min(tiles_m - band * GROUP_M, GROUP_M);
+  const int in_band = pid - band * GROUP_M * tiles_n;
+  const int m0 = (band * GROUP_M + in_band % band_rows) * BM;
+  const int n0 = (in_band / band_rows) * BN;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
+  const int lrow = lane & 31, lhi = (lane >> 5) * 4;
+
+  // running C: the old values, requested before anything else so that they arrive behind the first tiles
+  f32x16 c[MT][NT], acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const float* p0 = outf + (size_t)(m0 + wm + i * 32 + lhi) * N + n0 + wn + j * 32 + lrow;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        c[i][j][v] = p0[(size_t)((v >> 2) * 8 + (v & 3)) * N];
+        acc[i][j][v] = 0.f;
+      }
+      __builtin_amdgcn_sched_barrier(0);  // one tile's addresses at a time
+    }
+
+  const int spc = Kc / KS;        // steps per operand pair (even)
+  const int nk = ngroup * spc;
+  int g_next = 0, k_next = 0;  // operand pair and k offset of the next tile to fetch (tiles are fetched in order)
+  auto issue = [&](int it) {
+    const int nt = it + BS - 1;
+    if (nt < nk) {
+      dma_tr<BM>(gp.a[g_next], lda, m0, k_next, sA + (nt % BS) * C::A_ELEMS, wave, lane);
+      dma_tr<BN>(gp.b[g_next], ldb, n0, k_next, sB + (nt % BS) * C::B_ELEMS, wave, lane);
+      k_next += KS;
+      if (k_next == Kc) { k_next = 0; ++g_next; }
+    }
+  };
+  bf16x8 af1[MT], bf1[NT];  // fragments of a tile's second half, carried across the next barrier
+  auto load_frags = [&](int it, int kk, bf16x8 (&af)[MT], bf16x8 (&bfr)[NT]) {
+    const bf16_t* a_s = sA + (it % BS) * C::A_ELEMS;
+    const bf16_t* b_s = sB + (it % BS) * C::B_ELEMS;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) af[i] = frag_tr<BM>(a_s, wm + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) bfr[j] = frag_tr<BN>(b_s, wn + j * 32, kk, lane);
+  };
+  auto mfmas = [&](const bf16x8 (&af)[MT], const bf16x8 (&bfr)[NT]) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+  };
+  auto fold = [&]() {  // one operand pair is complete: add its product to the running C, start the next from zero
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          c[i][j][v] += acc[i][j][v];
+          acc[i][j][v] = 0.f;
+        }
+  };
+
+#pragma unroll
+  for (int it = 1 - BS; it < 0; ++it) issue(it);
+  int until_fold = spc;
+  for (int it = 0; it < nk; ++it) {
+    if (it + BS - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::allowed(0)));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();
+    bf16x8 af0[MT], bf0[NT];
+    load_frags(it, 0, af0, bf0);
+    if (it > 0) {
+      mfmas(af1, bf1);  // second half of step it-1, issued after this step's barrier
+      if (--until_fold == 0) { fold(); until_fold = spc; }
+    }
+    mfmas(af0, bf0);
+    load_frags(it, 1, af1, bf1);
+    issue(it);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragment reads done before the next barrier
+  }
+  mfmas(af1, bf1);
+  fold();
+
+  // the store addresses are worked out again here (from a copy of the tile origin the compiler cannot
+  // connect with the one used for the loads), or 64 address pairs would stay in registers across the loop
+  int m0s = m0, n0s = n0;
+  asm volatile("" : "+s"(m0s), "+s"(n0s));
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      float* p0 = outf + (size_t)(m0s + wm + i * 32 + lhi) * N + n0s + wn + j * 32 + lrow;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) p0[(size_t)((v >> 2) * 8 + (v & 3)) * N] = c[i][j][v];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // Few tiles and a long K (the N = hidden GEMMs of a 1024-token microbatch): cut K into slices so that
 // every CU gets a workgroup.  Returns false if the shape is not one for split-K.
 template <int MODE>
@@ -421,8 +548,39 @@ template <typename T> hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t
   return hipSuccess;
 }
 
+// grouped wgrad launch; *taken stays false if the shape is not one for the grouped kernel
+static hipError_t launch_wgrad_group(const GemmArgs& g, hipStream_t s, bool* taken) {
+  constexpr int BM = 128, BS = 5;
+  // below four pairs the lone workgroup per CU loses more in the main loop than it saves in epilogues
+  if (g.epilogue != EPI_ACCUM_F32 || g.group < 4 || g.group > kGemmGroupMax) return hipSuccess;
+  if (!(g.a_sm == 1 && g.b_sn == 1) || g.a_sk != g.M || g.b_sk != g.N) return hipSuccess;
+  if (g.M % BM != 0 || g.N % BN != 0 || g.K % 64 != 0 || !aligned16(g.outf)) return hipSuccess;
+  if ((long)g.M * g.N >= (1L << 31)) return hipSuccess;
+  GroupPtrs gp;
+  for (int i = 0; i < kGemmGroupMax; ++i) {
+    gp.a[i] = (const bf16_t*)g.group_a[i < g.group ? i : 0];
+    gp.b[i] = (const bf16_t*)g.group_b[i < g.group ? i : 0];
+    if (!gp.a[i] || !gp.b[i] || !aligned16(gp.a[i]) || !aligned16(gp.b[i])) return hipSuccess;
+  }
+  auto kern = gemm_wgrad_group_kernel<BM, BS>;
+  constexpr size_t smem = Cfg<BM, BS, true>::SMEM;
+  static_assert(smem <= 160 * 1024, "LDS budget");
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  *taken = true;
+  const int grid = (g.M / BM) * (g.N / BN);
+  kern<<<grid, NTHREADS, smem, s>>>(gp, g.group, g.M, g.N, g.K, (long)g.a_sk, (long)g.b_sk, g.outf);
+  return hipGetLastError();
+}
+
 template <> hipError_t launch_gemm_mfma<bf16_t>(const GemmArgs& g, hipStream_t s, bool* taken) {
   *taken = false;
+  if (g.group >= 2) return launch_wgrad_group(g, s, taken);
   const bool atr = g.a_sm == 1 && g.a_sk != 1, btr = g.b_sn == 1 && g.b_sk != 1;
   if (!btr) return hipSuccess;  // B must be row-contiguous
   const long lda = atr ? g.a_sk : g.a_sm, ldb = g.b_sk;

@@ -58,6 +58,7 @@ struct zb_stage {
   zb_config cfg;
   hipStream_t stream = nullptr;
   bool bf16 = true;
+  bool group_w = true;
   int L = 0, h = 0, a = 0, ffn = 0, s = 0, b = 0, T = 0, d = 0;
   size_t esz = 2;
 
@@ -165,6 +166,7 @@ size_t layout(zb_stage* st, void* arena) {
   st->L = c.layers; st->h = c.hidden; st->a = c.heads; st->ffn = c.ffn; st->s = c.seq; st->b = c.mb_size;
   st->T = c.seq * c.mb_size; st->d = c.hidden / c.heads;
   st->bf16 = c.dtype == ZB_BF16;
+  st->group_w = c.group_w != 0;
   st->esz = st->bf16 ? 2 : 4;
   const size_t h = st->h, f = st->ffn, T = st->T;
   const size_t pc[ZB_P_COUNT] = {h, h, h * 3 * h, 3 * h, h * h, h, h, h, h * f, f, f * h, h};
@@ -479,6 +481,48 @@ template <typename T> struct Exec {
     }
     return ZB_OK;
   }
+
+  // W of n microbatches (2 <= n <= kGemmGroupMax), parameter by parameter: one grouped wgrad GEMM per
+  // weight matrix, then the bias column sums microbatch by microbatch in the same order.
+  static zb_status backward_weight_group(zb_stage* st, const int* mbs, int n) {
+    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    hipStream_t s = st->stream;
+    const double E = sizeof(T);
+    for (int l = L - 1; l >= 0; --l) {
+      const LayerOff& q = st->lo[l];
+      struct Lin { size_t fw_off, bw_off; bool top_dy; int kin, nout, wi, bi; };
+      const Lin lins[4] = {{q.fw_g, q.bw_dy, l == L - 1, f, h, ZB_P_W2, ZB_P_B2},
+                           {q.fw_u, q.bw_dfh, false, h, f, ZB_P_W1, ZB_P_B1},
+                           {q.fw_c, q.bw_dy1, false, h, h, ZB_P_WO, ZB_P_BO},
+                           {q.fw_a, q.bw_dqkv, false, h, 3 * h, ZB_P_WQKV, ZB_P_BQKV}};
+      for (const Lin& ln : lins) {
+        GemmArgs g{};  // dW[kin, nout] += sum over the group of X^T dY, one product after the other
+        g.M = ln.kin; g.N = ln.nout; g.K = T_;
+        g.a_sm = 1; g.a_sk = ln.kin; g.b_sk = ln.nout; g.b_sn = 1;
+        g.epilogue = EPI_ACCUM_F32; g.outf = st->G(l, ln.wi);
+        g.group = n;
+        for (int i = 0; i < n; ++i) {
+          const int mb = mbs[i];
+          const char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
+          const char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
+          g.group_a[i] = fw + ln.fw_off;
+          g.group_b[i] = ln.top_dy ? (const char*)(st->in_dy + st->act_bytes * (size_t)mb) : bw + ln.bw_off;
+        }
+        g.A = g.group_a[0]; g.B = g.group_b[0];
+        {
+          ProfScope ps(st, KC_GEMM_WGRAD, 2.0 * g.M * g.N * g.K * n,
+                       8.0 * g.M * g.N + E * (double)g.K * ((double)g.M + g.N) * n);
+          ZB_HIP(st, launch_gemm<T>(g, s));
+        }
+        for (int i = 0; i < n; ++i) {
+          ProfScope ps(st, KC_COLSUM, 0, E * T_ * ln.nout);
+          ZB_HIP(st, launch_colsum_accum<T>((const T*)g.group_b[i], st->G(l, ln.bi), st->ln_partials, T_, ln.nout,
+                                            s));
+        }
+      }
+    }
+    return ZB_OK;
+  }
 };
 
 zb_status check_pass(zb_stage* st, int pass, int mb) {
@@ -555,6 +599,7 @@ zb_status zb_config_defaults(zb_config* cfg) {
   cfg->mb_size = 1;
   cfg->dtype = ZB_BF16;
   cfg->journal = 1;
+  cfg->group_w = 1;
   cfg->ln_eps = 1e-5f;
   cfg->lr = 1e-4f; cfg->beta1 = 0.9f; cfg->beta2 = 0.95f; cfg->adam_eps = 1e-8f; cfg->weight_decay = 0.01f;
   cfg->clip = 1.0f;
@@ -671,6 +716,54 @@ zb_status zb_backward_weight(zb_stage* st, int32_t mb) {
   return ZB_OK;
 }
 
+zb_status zb_backward_weight_group(zb_stage* st, const int32_t* mbs, int32_t n) {
+  if (!st) return ZB_EINVAL;
+  if (!mbs || n < 1) return fail(st, ZB_EINVAL, "no microbatches given");
+  if (n == 1) return zb_backward_weight(st, mbs[0]);
+  for (int i = 0; i < n; ++i) {
+    zb_status rc = check_pass(st, ZB_PASS_W, mbs[i]);
+    if (rc != ZB_OK) return rc;
+    for (int j = 0; j < i; ++j)
+      if (mbs[j] == mbs[i]) return fail(st, ZB_EORDER, "a microbatch appears twice in the group");
+  }
+  for (int i0 = 0; i0 < n; i0 += kGemmGroupMax) {  // at most kGemmGroupMax operand pairs per GEMM
+    const int cnt = n - i0 < kGemmGroupMax ? n - i0 : kGemmGroupMax;
+    zb_status rc;
+    if (cnt == 1) rc = st->bf16 ? Exec<bf16_t>::backward_weight(st, mbs[i0]) : Exec<float>::backward_weight(st, mbs[i0]);
+    else rc = st->bf16 ? Exec<bf16_t>::backward_weight_group(st, mbs + i0, cnt)
+                       : Exec<float>::backward_weight_group(st, mbs + i0, cnt);
+    if (rc != ZB_OK) return rc;
+    for (int i = i0; i < i0 + cnt; ++i) {
+      const int mb = mbs[i];
+      st->done[ZB_PASS_W][mb] = 1;
+      st->free_fw.push_back(st->slot_fw[mb]);
+      st->free_bw.push_back(st->slot_bw[mb]);
+      st->slot_fw[mb] = st->slot_bw[mb] = -1;
+    }
+  }
+  return ZB_OK;
+}
+
+// Runs a stage order; with group_w, maximal runs of consecutive W entries go through the grouped W.
+static zb_status run_ops(zb_stage* st, const zb_op* ops, size_t n) {
+  std::vector<int32_t> run;
+  for (size_t q = 0; q < n;) {
+    const zb_op& op = ops[q];
+    if (op.pass == ZB_PASS_W && st->group_w) {
+      run.clear();
+      while (q < n && ops[q].pass == ZB_PASS_W) run.push_back(ops[q++].mb);
+      zb_status rc = zb_backward_weight_group(st, run.data(), (int32_t)run.size());
+      if (rc != ZB_OK) return rc;
+      continue;
+    }
+    zb_status rc = op.pass == ZB_PASS_F ? zb_forward(st, op.mb)
+                 : op.pass == ZB_PASS_B ? zb_backward_input(st, op.mb) : zb_backward_weight(st, op.mb);
+    if (rc != ZB_OK) return rc;
+    ++q;
+  }
+  return ZB_OK;
+}
+
 zb_status zb_schedule_order(int32_t p, int32_t stage, int32_t m, int32_t kind, zb_op* out, int32_t cap,
                             int32_t* n) {
   if (!n || check_sched_args(p, stage, m, kind) != ZB_OK) return ZB_EINVAL;
@@ -736,13 +829,7 @@ zb_status zb_run_order(zb_stage* st, const zb_op* ops, int32_t n) {
   if (!ops || n < 0) return fail(st, ZB_EINVAL, "no order given");
   if (n != 3 * st->m) return fail(st, ZB_ESTATE, "the order must hold 3m passes for zb_begin_iteration's m");
   if (!valid_stage_order(ops, n)) return fail(st, ZB_EORDER, "not a valid stage order");
-  for (int q = 0; q < n; ++q) {
-    const zb_op& op = ops[q];
-    zb_status rc = op.pass == ZB_PASS_F ? zb_forward(st, op.mb)
-                 : op.pass == ZB_PASS_B ? zb_backward_input(st, op.mb) : zb_backward_weight(st, op.mb);
-    if (rc != ZB_OK) return rc;
-  }
-  return ZB_OK;
+  return run_ops(st, ops, (size_t)n);
 }
 
 zb_status zb_run_schedule(zb_stage* st, int32_t p, int32_t stage, int32_t m, int32_t kind) {
@@ -752,12 +839,7 @@ zb_status zb_run_schedule(zb_stage* st, int32_t p, int32_t stage, int32_t m, int
   if (m != st->m) return fail(st, ZB_ESTATE, "m differs from zb_begin_iteration's");
   std::vector<zb_op> ops;
   build_order(p, stage, m, kind, &ops);
-  for (const zb_op& op : ops) {
-    zb_status rc = op.pass == ZB_PASS_F ? zb_forward(st, op.mb)
-                 : op.pass == ZB_PASS_B ? zb_backward_input(st, op.mb) : zb_backward_weight(st, op.mb);
-    if (rc != ZB_OK) return rc;
-  }
-  return ZB_OK;
+  return run_ops(st, ops.data(), ops.size());
 }
 
 zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, zb_step_report* report) {

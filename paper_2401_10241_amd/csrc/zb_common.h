@@ -74,7 +74,14 @@ struct GemmArgs {
   const void* aux;     // resid or pre-activation, [M,N] type T
   float* workspace;    // optional fp32 scratch for split-K partial products (device), may be null
   size_t workspace_floats;
+  // Grouped wgrad (EPI_ACCUM_F32 only): group >= 2 operand pairs of the same shape and strides;
+  // outf = (((outf + A_0^T B_0) + A_1^T B_1) + ...), each product rounded to fp32 before it is added,
+  // i.e. bit for bit what `group` separate launches give.  A and B above are ignored then.
+  int group;
+  const void* group_a[16];
+  const void* group_b[16];
 };
+constexpr int kGemmGroupMax = 16;
 
 template <typename T> hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 
