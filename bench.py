@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--m", type=int, default=0, help="override the number of microbatches (debug)")
+    ap.add_argument("--order", default="workload", choices=["workload", "1F1B", "1F1B-fused"],
+                    help="per-stage order: the workload's ZB-H1 / ZB-H2 (default), 1F1B with B and W as separate "
+                         "passes, or 1F1B with the traditional single backward (B and W fused layer by layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -129,8 +132,9 @@ def main():
         w = w.scaled(m=args.m)
     m = w.m
     torch.cuda.set_device(0)
-    pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, w.kind)
-    st = zb.Stage(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+    kind = w.kind if args.order == "workload" else "1F1B"
+    pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, kind)
+    st = zb.Stage(fuse_bw=(args.order == "1F1B-fused"), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
                   dtype=w.dtype, max_microbatches=m, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
                   lr=w.lr, beta1=w.beta1, beta2=w.beta2, adam_eps=w.adam_eps, weight_decay=w.weight_decay,
                   clip=w.clip, ln_eps=w.ln_eps)
@@ -147,7 +151,7 @@ def main():
         it = it_counter[0]
         it_counter[0] += 1
         st.begin_iteration(it, m)
-        st.run_schedule(w.p, w.stage, m, w.kind)
+        st.run_schedule(w.p, w.stage, m, kind)
         if w.optimizer:
             st.optimizer_step_validated(0.0, zb_inputs.rest_state(w, it), want_report=False)
 
@@ -178,7 +182,9 @@ def main():
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
-        "config": {"workload": f"{w.name}: stage {w.stage} of p={w.p}, ZB-{w.kind} order, m={m}, {w.layers} GPT "
+        "config": {"workload": f"{w.name}: stage {w.stage} of p={w.p}, "
+                               + (f"ZB-{w.kind}" if args.order == "workload" else args.order)
+                               + f" order, m={m}, {w.layers} GPT "
                                f"decoder layers h={w.hidden} a={w.heads} ffn={w.ffn} seq={w.seq} b={w.mb_size}"
                                + (", validated AdamW step" if w.optimizer else ""),
                    "model_flops_per_step": flops, "setup_seconds": round(setup_s, 1)},

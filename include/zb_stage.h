@@ -92,6 +92,8 @@ typedef struct {
                                Algorithm 1's arithmetic inverse only (exact to rounding) */
   int32_t group_w;          /* 1: zb_run_schedule / zb_run_order run consecutive W passes of the order as
                                one grouped W (zb_backward_weight_group); 0: one by one.  Same bits. */
+  int32_t fuse_bw;          /* 1: where an order has W_k directly after B_k (1F1B), zb_run_schedule /
+                               zb_run_order run the two as one zb_backward_fused; 0 (default): separately */
   float ln_eps;             /* 1e-5 */
   float lr, beta1, beta2, adam_eps, weight_decay; /* Algorithm 1's gamma, beta1, beta2, eps, lambda */
   float clip;               /* global gradient-norm clipping threshold (Sec. 4) */
@@ -127,6 +129,12 @@ zb_status zb_begin_iteration(zb_stage* st, int32_t iter, int32_t m);
 zb_status zb_forward(zb_stage* st, int32_t mb);
 zb_status zb_backward_input(zb_stage* st, int32_t mb);
 zb_status zb_backward_weight(zb_stage* st, int32_t mb);
+
+/* B and W of microbatch mb as the traditional single backward (Sec. 1: 1F1B's backward, before the split):
+ * layer by layer from the last to the first, the input gradient of a layer and right after it that layer's
+ * parameter gradients.  Same results, bit for bit, as zb_backward_input(mb) then zb_backward_weight(mb);
+ * it is here to measure what the split costs or gains on one GPU.  Needs a free B->W stash slot. */
+zb_status zb_backward_fused(zb_stage* st, int32_t mb);
 
 /* W of n microbatches at once, mbs[0..n) (host) in that order, grouped by parameter (Appendix A groups
  * the deferred W passes by parameter; Sec. 2: W may run anywhere after its B): every weight gradient is

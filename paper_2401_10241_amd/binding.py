@@ -47,7 +47,7 @@ class zb_config(C.Structure):
     _fields_ = [("layers", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32), ("ffn", C.c_int32),
                 ("seq", C.c_int32), ("mb_size", C.c_int32), ("max_microbatches", C.c_int32),
                 ("max_pending_b", C.c_int32), ("max_pending_w", C.c_int32), ("max_inflight", C.c_int32),
-                ("dtype", C.c_int32), ("journal", C.c_int32), ("group_w", C.c_int32), ("ln_eps", C.c_float), ("lr", C.c_float),
+                ("dtype", C.c_int32), ("journal", C.c_int32), ("group_w", C.c_int32), ("fuse_bw", C.c_int32), ("ln_eps", C.c_float), ("lr", C.c_float),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
                 ("weight_decay", C.c_float), ("clip", C.c_float), ("hip_stream", C.c_void_p),
                 ("arena", C.c_void_p), ("arena_bytes", C.c_size_t)]
@@ -89,6 +89,7 @@ _sig = {
     "zb_backward_input": [C.c_void_p, C.c_int32],
     "zb_backward_weight": [C.c_void_p, C.c_int32],
     "zb_backward_weight_group": [C.c_void_p, _P(C.c_int32), C.c_int32],
+    "zb_backward_fused": [C.c_void_p, C.c_int32],
     "zb_schedule_order": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P(zb_op), C.c_int32, _P(C.c_int32)],
     "zb_schedule_stash_need": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P(C.c_int32), _P(C.c_int32),
                                _P(C.c_int32)],
@@ -243,7 +244,7 @@ class Stage:
     """One pipeline stage living on the current CUDA/HIP device."""
 
     def __init__(self, *, layers, hidden, heads, ffn, seq, mb_size=1, dtype="bf16", max_microbatches,
-                 max_pending_b, max_pending_w, max_inflight, journal=True, group_w=True, ln_eps=1e-5, lr=1e-4, beta1=0.9,
+                 max_pending_b, max_pending_w, max_inflight, journal=True, group_w=True, fuse_bw=False, ln_eps=1e-5, lr=1e-4, beta1=0.9,
                  beta2=0.95, adam_eps=1e-8, weight_decay=0.01, clip=1.0, device="cuda:0", stream=None):
         import torch
         if not torch.cuda.is_available():
@@ -258,6 +259,7 @@ class Stage:
         cfg.dtype = BF16 if dtype == "bf16" else FP32
         cfg.journal = 1 if journal else 0
         cfg.group_w = 1 if group_w else 0
+        cfg.fuse_bw = 1 if fuse_bw else 0
         cfg.ln_eps, cfg.lr, cfg.beta1, cfg.beta2 = ln_eps, lr, beta1, beta2
         cfg.adam_eps, cfg.weight_decay, cfg.clip = adam_eps, weight_decay, clip
         need = C.c_size_t(0)
@@ -314,6 +316,9 @@ class Stage:
 
     def backward_weight(self, mb: int):
         self._call(lib.zb_backward_weight, mb)
+
+    def backward_fused(self, mb: int):
+        self._call(lib.zb_backward_fused, mb)
 
     def backward_weight_group(self, mbs):
         arr = (C.c_int32 * max(len(mbs), 1))(*[int(k) for k in mbs])

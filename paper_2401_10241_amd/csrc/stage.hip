@@ -59,6 +59,7 @@ struct zb_stage {
   hipStream_t stream = nullptr;
   bool bf16 = true;
   bool group_w = true;
+  bool fuse_bw = false;
   int L = 0, h = 0, a = 0, ffn = 0, s = 0, b = 0, T = 0, d = 0;
   size_t esz = 2;
 
@@ -167,6 +168,7 @@ size_t layout(zb_stage* st, void* arena) {
   st->T = c.seq * c.mb_size; st->d = c.hidden / c.heads;
   st->bf16 = c.dtype == ZB_BF16;
   st->group_w = c.group_w != 0;
+  st->fuse_bw = c.fuse_bw != 0;
   st->esz = st->bf16 ? 2 : 4;
   const size_t h = st->h, f = st->ffn, T = st->T;
   const size_t pc[ZB_P_COUNT] = {h, h, h * 3 * h, 3 * h, h * h, h, h, h, h * f, f, f * h, h};
@@ -388,17 +390,20 @@ template <typename T> struct Exec {
     return ZB_OK;
   }
 
-  static zb_status backward_input(zb_stage* st, int mb) {
+  // layers l_hi down to l_lo (the whole stack by default)
+  static zb_status backward_input(zb_stage* st, int mb, int l_hi = -1, int l_lo = 0) {
     const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
     char* fb = st->fb_pool + st->fb_slot * (size_t)st->slot_fb[mb];
     char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
     char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
-    const T* dy = (const T*)(st->in_dy + st->act_bytes * (size_t)mb);
     T* tmp = (T*)st->tmp;
     const double E = sizeof(T);
-    for (int l = L - 1; l >= 0; --l) {
+    if (l_hi < 0) l_hi = L - 1;
+    for (int l = l_hi; l >= l_lo; --l) {
       const LayerOff& q = st->lo[l];
+      // gradient entering layer l: the stage's upstream gradient, or what layer l+1 left in the B->W stash
+      const T* dy = l == L - 1 ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
       const T* xl = l == 0 ? (const T*)(st->in_x + st->act_bytes * (size_t)mb) : (const T*)(fb + q.fb_x);
       const T* QKV = (const T*)(fb + q.fb_qkv);
       const T* Y1 = (const T*)(fb + q.fb_y1);
@@ -449,18 +454,18 @@ template <typename T> struct Exec {
         ZB_HIP(st, launch_layernorm_bwd<T>(tmp, xl, st1, st->P(l, ZB_P_LN1_G), dY1, dx, st->G(l, ZB_P_LN1_G),
                                             st->G(l, ZB_P_LN1_B), st->ln_partials, T_, h, s));
       }
-      dy = dx;
     }
     return ZB_OK;
   }
 
-  static zb_status backward_weight(zb_stage* st, int mb) {
+  static zb_status backward_weight(zb_stage* st, int mb, int l_hi = -1, int l_lo = 0) {
     const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
     char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
     char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
     const double E = sizeof(T);
-    for (int l = L - 1; l >= 0; --l) {
+    if (l_hi < 0) l_hi = L - 1;
+    for (int l = l_hi; l >= l_lo; --l) {
       const LayerOff& q = st->lo[l];
       const T* dyl = l == L - 1 ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
       struct Pair { const T* x; const T* dy; int kin, nout, wi, bi; };
@@ -478,6 +483,17 @@ template <typename T> struct Exec {
         ProfScope ps(st, KC_COLSUM, 0, E * T_ * pr.nout);
         ZB_HIP(st, launch_colsum_accum<T>(pr.dy, st->G(l, pr.bi), st->ln_partials, T_, pr.nout, s));
       }
+    }
+    return ZB_OK;
+  }
+
+  // The traditional single backward (Sec. 1): layer by layer, the input gradient and right after it the
+  // parameter gradients of the same layer, while that layer's output gradients are still in the caches.
+  static zb_status backward_fused(zb_stage* st, int mb) {
+    for (int l = st->L - 1; l >= 0; --l) {
+      zb_status rc = backward_input(st, mb, l, l);
+      if (rc != ZB_OK) return rc;
+      if ((rc = backward_weight(st, mb, l, l)) != ZB_OK) return rc;
     }
     return ZB_OK;
   }
@@ -716,6 +732,21 @@ zb_status zb_backward_weight(zb_stage* st, int32_t mb) {
   return ZB_OK;
 }
 
+zb_status zb_backward_fused(zb_stage* st, int32_t mb) {
+  zb_status rc = check_pass(st, ZB_PASS_B, mb);
+  if (rc != ZB_OK) return rc;
+  if (st->free_bw.empty()) return fail(st, ZB_ENOMEM, "no free stash slot for B: raise max_pending_w");
+  st->slot_bw[mb] = take_slot(st->free_bw);
+  rc = st->bf16 ? Exec<bf16_t>::backward_fused(st, mb) : Exec<float>::backward_fused(st, mb);
+  if (rc != ZB_OK) return rc;
+  st->done[ZB_PASS_B][mb] = st->done[ZB_PASS_W][mb] = 1;
+  st->free_fb.push_back(st->slot_fb[mb]);
+  st->free_fw.push_back(st->slot_fw[mb]);
+  st->free_bw.push_back(st->slot_bw[mb]);
+  st->slot_fb[mb] = st->slot_fw[mb] = st->slot_bw[mb] = -1;
+  return ZB_OK;
+}
+
 zb_status zb_backward_weight_group(zb_stage* st, const int32_t* mbs, int32_t n) {
   if (!st) return ZB_EINVAL;
   if (!mbs || n < 1) return fail(st, ZB_EINVAL, "no microbatches given");
@@ -754,6 +785,12 @@ static zb_status run_ops(zb_stage* st, const zb_op* ops, size_t n) {
       while (q < n && ops[q].pass == ZB_PASS_W) run.push_back(ops[q++].mb);
       zb_status rc = zb_backward_weight_group(st, run.data(), (int32_t)run.size());
       if (rc != ZB_OK) return rc;
+      continue;
+    }
+    if (st->fuse_bw && op.pass == ZB_PASS_B && q + 1 < n && ops[q + 1].pass == ZB_PASS_W && ops[q + 1].mb == op.mb) {
+      zb_status rc = zb_backward_fused(st, op.mb);  // B_k W_k: the single backward of 1F1B
+      if (rc != ZB_OK) return rc;
+      q += 2;
       continue;
     }
     zb_status rc = op.pass == ZB_PASS_F ? zb_forward(st, op.mb)

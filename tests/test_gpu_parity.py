@@ -146,6 +146,51 @@ def test_grouped_w_has_the_bits_of_one_by_one_w(shape):
         assert g.tobytes() == results[0].tobytes()
 
 
+def test_fused_backward_has_the_bits_of_b_then_w():
+    # the traditional single backward (layer by layer: input gradient, then that layer's parameter
+    # gradients) against B then W of the split, bit for bit, and against the oracle
+    import paper_2401_10241_amd as zb
+    m = 4
+    w = W("fused", "bf16", 3, 256, 4, 1024, 128, 1, 4, 2, m, "H1", seed=29)
+    params = zb_inputs.stage_params(w)
+    order = zb.schedule_order(4, 2, m, "1F1B")
+    results = []
+    for mode in ("split", "fused calls", "run_schedule with fuse_bw"):
+        dev = make_device_stage(w, m, pools=(m, m, m), **({"fuse_bw": True} if mode.startswith("run") else {}))
+        dev.set_params(params)
+        dev.begin_iteration(0, m)
+        load_iteration(w, 0, m, dev)
+        if mode == "split":
+            for c, k in order:
+                (dev.forward, dev.backward_input, dev.backward_weight)[c](k)
+        elif mode == "fused calls":
+            for c, k in order:
+                if c == 0:
+                    dev.forward(k)
+                elif c == 1:
+                    dev.backward_fused(k)
+            with pytest.raises(zb.ZbError) as e:
+                dev.backward_weight(0)                  # the fused call did W too
+            assert e.value.status == zb.EORDER
+        else:
+            dev.run_schedule(4, 2, m, "1F1B")
+        dev.synchronize()
+        results.append((dev.get_tensor(zb.T_FLAT_GRADS).copy(),
+                        [dev.get_tensor(zb.T_OUTPUT_DX, 0, k).copy() for k in range(m)]))
+        if mode == "fused calls":
+            orc = make_oracle(w, params)
+            orc.begin_iteration(m)
+            load_iteration(w, 0, m, orc=orc)
+            orc.run(order)
+            compare_outputs(dev, orc, m, TOL["bf16"])
+            compare_grads(dev, orc, TOL["bf16"])
+        dev.close()
+    for g, dxs in results[1:]:
+        assert g.tobytes() == results[0][0].tobytes()
+        for a, b in zip(dxs, results[0][1]):
+            assert a.tobytes() == b.tobytes()
+
+
 def test_pass_order_is_enforced():
     import paper_2401_10241_amd as zb
     w = W("ord", "fp32", 1, 64, 2, 256, 32, 1, 2, 0, 2, "H1", seed=3)

@@ -20,13 +20,13 @@ def hyper(w):
     return O.Hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.adam_eps, weight_decay=w.weight_decay, clip=w.clip)
 
 
-def make_device_stage(w, m=None, pools=None, journal=True, group_w=True):
+def make_device_stage(w, m=None, pools=None, journal=True, group_w=True, fuse_bw=False):
     import paper_2401_10241_amd as zb
     m = m or w.m
     pb, pw, fl = pools or zb.schedule_stash_need(w.p, w.stage, m, w.kind)
     return zb.Stage(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
                     dtype=w.dtype, max_microbatches=m, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
-                    journal=journal, group_w=group_w, ln_eps=w.ln_eps, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
+                    journal=journal, group_w=group_w, fuse_bw=fuse_bw, ln_eps=w.ln_eps, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
                     adam_eps=w.adam_eps, weight_decay=w.weight_decay, clip=w.clip)
 
 
