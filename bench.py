@@ -87,6 +87,8 @@ def auto_schedule_report(zb, st, w, m, class_ms):
         orders = [zb.schedule_order(p, i, m, kind) for i in range(p)]
         rates["1F1B" if kind == "1F1B" else "ZB-" + kind] = round(
             zb.simulate_pipeline(orders, t_f, t_b, t_w, t_comm, fused_backward=(kind == "1F1B"))[1], 4)
+    # ZB-V: every stage as two chunks, each chunk's pass taking half the stage's time
+    rates["ZB-V"] = round(zb.simulate_pipeline_v(zb.schedule_order_v(p, m), m, t_f / 2, t_b / 2, t_w / 2, t_comm)[1], 4)
     t0 = time.perf_counter()
     found = {}
     for name, mult in (("auto, limit p*M_B", 1), ("auto, limit 2p*M_B", 2)):
@@ -108,9 +110,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--m", type=int, default=0, help="override the number of microbatches (debug)")
-    ap.add_argument("--order", default="workload", choices=["workload", "1F1B", "1F1B-fused"],
+    ap.add_argument("--order", default="workload", choices=["workload", "1F1B", "1F1B-fused", "ZB-V"],
                     help="per-stage order: the workload's ZB-H1 / ZB-H2 (default), 1F1B with B and W as separate "
-                         "passes, or 1F1B with the traditional single backward (B and W fused layer by layer)")
+                         "passes, 1F1B with the traditional single backward (B and W fused layer by layer), or ZB-V "
+                         "(Sec. 6: the stage's layers as two chunks, 2m virtual microbatches; needs an even "
+                         "number of layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -133,14 +137,23 @@ def main():
     m = w.m
     torch.cuda.set_device(0)
     kind = w.kind if args.order == "workload" else "1F1B"
-    pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, kind)
-    st = zb.Stage(fuse_bw=(args.order == "1F1B-fused"), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
-                  dtype=w.dtype, max_microbatches=m, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
+    zbv = args.order == "ZB-V"
+    if zbv:
+        if w.layers % 2:
+            print(f"bench.py: ZB-V splits the stage's layers into two chunks; {w.name} has {w.layers}", file=sys.stderr)
+            sys.exit(2)
+        v_ops = zb.schedule_order_v(w.p, m)[w.stage]
+        pb, pw, fl = zb.order_stash_need(v_ops)
+    else:
+        pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, kind)
+    m_run = 2 * m if zbv else m          # virtual microbatches (chunk * m + microbatch) under ZB-V
+    st = zb.Stage(fuse_bw=(args.order == "1F1B-fused"), chunks=(2 if zbv else 1), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+                  dtype=w.dtype, max_microbatches=m_run, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
                   lr=w.lr, beta1=w.beta1, beta2=w.beta2, adam_eps=w.adam_eps, weight_decay=w.weight_decay,
                   clip=w.clip, ln_eps=w.ln_eps)
     t0 = time.perf_counter()
     st.set_params(zb_inputs.stage_params(w))
-    for k in range(m):
+    for k in range(m_run):
         st.set_tensor(zb.T_INPUT_X, 0, k, zb_inputs.stage_input(w, 0, k))
         st.set_tensor(zb.T_INPUT_DY, 0, k, zb_inputs.upstream_grad(w, 0, k))
     setup_s = time.perf_counter() - t0
@@ -150,8 +163,11 @@ def main():
     def step():
         it = it_counter[0]
         it_counter[0] += 1
-        st.begin_iteration(it, m)
-        st.run_schedule(w.p, w.stage, m, kind)
+        st.begin_iteration(it, m_run)
+        if zbv:
+            st.run_order(v_ops)
+        else:
+            st.run_schedule(w.p, w.stage, m, kind)
         if w.optimizer:
             st.optimizer_step_validated(0.0, zb_inputs.rest_state(w, it), want_report=False)
 
@@ -173,7 +189,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
-    flops = st.model_flops(m)
+    flops = st.model_flops(m_run)
     value = flops / (ms_per_step * 1e-3) / 1e12
 
     out = {

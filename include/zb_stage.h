@@ -94,6 +94,10 @@ typedef struct {
                                one grouped W (zb_backward_weight_group); 0: one by one.  Same bits. */
   int32_t fuse_bw;          /* 1: where an order has W_k directly after B_k (1F1B), zb_run_schedule /
                                zb_run_order run the two as one zb_backward_fused; 0 (default): separately */
+  int32_t chunks;           /* 1, or 2 for ZB-V (Sec. 6): the first half of the layers is chunk 0, the second
+                               half chunk 1; microbatch indices are then VIRTUAL, v = chunk * (m/2) + microbatch
+                               for zb_begin_iteration's (even) m, each with its own INPUT_X / INPUT_DY /
+                               OUTPUT_Y / OUTPUT_DX, and a pass on v runs through the layers of its chunk only */
   float ln_eps;             /* 1e-5 */
   float lr, beta1, beta2, adam_eps, weight_decay; /* Algorithm 1's gamma, beta1, beta2, eps, lambda */
   float clip;               /* global gradient-norm clipping threshold (Sec. 4) */
@@ -193,6 +197,21 @@ zb_status zb_auto_schedule(int32_t p, int32_t m, const zb_pass_times* times, con
 zb_status zb_auto_schedule_search(int32_t p, int32_t m, const zb_pass_times* times, const zb_memory_model* mem,
                                   zb_op* orders, double* cost, double* bubble_rate, int32_t* extra_warmup_f,
                                   int32_t* skip_f);
+
+/* ZB-V (Sec. 6): every worker holds two chunks, chunk 0 of workers 1..p followed by chunk 1 of workers
+ * p..1 makes the model.  An entry names a VIRTUAL microbatch v = chunk * m + microbatch, so a worker's
+ * order has 6m entries over 2m virtual microbatches; orders[p * 6m] (host) receives all workers' orders
+ * (warm-up of 2p-1 forwards, F-B-W groups per chunk, then the remaining B and W with B first and W filling
+ * the gaps, built for equal pass times).  With m >= 2p-1 and equal pass times no worker idles, and no
+ * worker holds more than 2p chunk activations (= p M_B). */
+zb_status zb_schedule_order_v(int32_t p, int32_t m, zb_op* orders);
+
+/* Timing model for such orders: F of chunk 0 waits for worker-1, F of chunk 1 for worker+1 (the last
+ * worker: for its own chunk 0), B of chunk 1 for worker-1 (the first worker: for its own F of chunk 1),
+ * B of chunk 0 for worker+1 (the last worker: for its own B of chunk 1).  times are those of ONE chunk's
+ * pass; *bubble_rate = (cost - 2m(T_F+T_B+T_W)) / cost.  Out pointers may be NULL. */
+zb_status zb_simulate_pipeline_v(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times, double* cost,
+                                 double* bubble_rate, double* stage_span);
 
 /* Peak of Appendix G's memory walk over one stage order of n entries. */
 zb_status zb_order_memory_peak(const zb_op* ops, int32_t n, double m_b, double m_w, double* peak);

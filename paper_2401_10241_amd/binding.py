@@ -47,7 +47,7 @@ class zb_config(C.Structure):
     _fields_ = [("layers", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32), ("ffn", C.c_int32),
                 ("seq", C.c_int32), ("mb_size", C.c_int32), ("max_microbatches", C.c_int32),
                 ("max_pending_b", C.c_int32), ("max_pending_w", C.c_int32), ("max_inflight", C.c_int32),
-                ("dtype", C.c_int32), ("journal", C.c_int32), ("group_w", C.c_int32), ("fuse_bw", C.c_int32), ("ln_eps", C.c_float), ("lr", C.c_float),
+                ("dtype", C.c_int32), ("journal", C.c_int32), ("group_w", C.c_int32), ("fuse_bw", C.c_int32), ("chunks", C.c_int32), ("ln_eps", C.c_float), ("lr", C.c_float),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
                 ("weight_decay", C.c_float), ("clip", C.c_float), ("hip_stream", C.c_void_p),
                 ("arena", C.c_void_p), ("arena_bytes", C.c_size_t)]
@@ -103,6 +103,9 @@ _sig = {
     "zb_auto_schedule_search": [C.c_int32, C.c_int32, _P(zb_pass_times), _P(zb_memory_model), _P(zb_op),
                                 _P(C.c_double), _P(C.c_double), _P(C.c_int32), _P(C.c_int32)],
     "zb_order_memory_peak": [_P(zb_op), C.c_int32, C.c_double, C.c_double, _P(C.c_double)],
+    "zb_schedule_order_v": [C.c_int32, C.c_int32, _P(zb_op)],
+    "zb_simulate_pipeline_v": [C.c_int32, C.c_int32, _P(zb_op), _P(zb_pass_times), _P(C.c_double), _P(C.c_double),
+                               _P(C.c_double)],
     "zb_optimizer_step_validated": [C.c_void_p, _P(zb_global_state), _P(zb_step_report)],
     "zb_get_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
     "zb_set_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
@@ -216,6 +219,29 @@ def auto_schedule_search(p: int, m: int, t_f: float, t_b: float, t_w: float, t_c
     return _unpack_orders(buf, p, m), cost.value, rate.value, (bool(ew.value), bool(sk.value))
 
 
+def schedule_order_v(p: int, m: int) -> List[List[Tuple[int, int]]]:
+    """zb_schedule_order_v: ZB-V orders of all p workers as (pass, virtual microbatch = chunk * m + mb)."""
+    buf = (zb_op * max(6 * p * m, 1))()
+    rc = lib.zb_schedule_order_v(p, m, buf)
+    if rc != OK:
+        raise ZbError(rc, "zb_schedule_order_v")
+    return [[(buf[i * 6 * m + q].pass_, buf[i * 6 * m + q].mb) for q in range(6 * m)] for i in range(p)]
+
+
+def simulate_pipeline_v(orders, m: int, t_f: float, t_b: float, t_w: float,
+                        t_comm: float = 0.0) -> Tuple[float, float, List[float]]:
+    """zb_simulate_pipeline_v: (cost, bubble rate, per-worker spans); times of one chunk's pass."""
+    p = len(orders)
+    buf = _pack_order([op for o in orders for op in o])
+    t = zb_pass_times(t_f, t_b, t_w, t_comm)
+    cost, rate = C.c_double(0), C.c_double(0)
+    spans = (C.c_double * p)()
+    rc = lib.zb_simulate_pipeline_v(p, m, buf, C.byref(t), C.byref(cost), C.byref(rate), spans)
+    if rc != OK:
+        raise ZbError(rc, "zb_simulate_pipeline_v")
+    return cost.value, rate.value, list(spans)
+
+
 def order_memory_peak(ops, m_b: float, m_w: float) -> float:
     """zb_order_memory_peak."""
     peak = C.c_double(0)
@@ -244,7 +270,7 @@ class Stage:
     """One pipeline stage living on the current CUDA/HIP device."""
 
     def __init__(self, *, layers, hidden, heads, ffn, seq, mb_size=1, dtype="bf16", max_microbatches,
-                 max_pending_b, max_pending_w, max_inflight, journal=True, group_w=True, fuse_bw=False, ln_eps=1e-5, lr=1e-4, beta1=0.9,
+                 max_pending_b, max_pending_w, max_inflight, journal=True, group_w=True, fuse_bw=False, chunks=1, ln_eps=1e-5, lr=1e-4, beta1=0.9,
                  beta2=0.95, adam_eps=1e-8, weight_decay=0.01, clip=1.0, device="cuda:0", stream=None):
         import torch
         if not torch.cuda.is_available():
@@ -260,6 +286,7 @@ class Stage:
         cfg.journal = 1 if journal else 0
         cfg.group_w = 1 if group_w else 0
         cfg.fuse_bw = 1 if fuse_bw else 0
+        cfg.chunks = chunks
         cfg.ln_eps, cfg.lr, cfg.beta1, cfg.beta2 = ln_eps, lr, beta1, beta2
         cfg.adam_eps, cfg.weight_decay, cfg.clip = adam_eps, weight_decay, clip
         need = C.c_size_t(0)

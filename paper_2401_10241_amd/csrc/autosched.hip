@@ -302,6 +302,140 @@ zb_status zb_auto_schedule_search(int32_t p, int32_t m, const zb_pass_times* tim
   return ZB_OK;
 }
 
+// ---- ZB-V (Sec. 6): two chunks per worker, virtual microbatch v = chunk * m + microbatch ------------
+
+namespace {
+
+struct VDep { int worker, pass, v; bool link, none; };
+
+// whose end worker i (0-based) waits for before (pass, chunk, k); chunk 0 runs worker 0..p-1, chunk 1 back
+VDep v_producer(int p, int m, int i, int pass, int ch, int k) {
+  if (pass == ZB_PASS_F) {
+    if (ch == 0) return i == 0 ? VDep{0, 0, 0, false, true} : VDep{i - 1, ZB_PASS_F, k, true, false};
+    return i < p - 1 ? VDep{i + 1, ZB_PASS_F, m + k, true, false} : VDep{i, ZB_PASS_F, k, false, false};
+  }
+  if (pass == ZB_PASS_B) {
+    if (ch == 1) return i > 0 ? VDep{i - 1, ZB_PASS_B, m + k, true, false} : VDep{i, ZB_PASS_F, m + k, false, false};
+    return i < p - 1 ? VDep{i + 1, ZB_PASS_B, k, true, false} : VDep{i, ZB_PASS_B, m + k, false, false};
+  }
+  return VDep{i, ZB_PASS_B, ch * m + k, false, false};
+}
+
+// phases 1 and 2 of worker sigma + 1: warm-up forwards, then F-B-W groups of one chunk
+void v_static_part(int p, int sigma, int m, std::vector<zb_op>* ops) {
+  const int i = sigma + 1;
+  int nf[2] = {0, 0}, nb[2] = {0, 0}, nw[2] = {0, 0};
+  auto f = [&](int c) { if (nf[c] < m) ops->push_back(zb_op{ZB_PASS_F, c * m + nf[c]++}); };
+  auto b = [&](int c) { if (nb[c] < nf[c]) ops->push_back(zb_op{ZB_PASS_B, c * m + nb[c]++}); };
+  auto w = [&](int c) { if (nw[c] < nb[c]) ops->push_back(zb_op{ZB_PASS_W, c * m + nw[c]++}); };
+  for (int q = 0; q < 2 * (p - i) + 1; ++q) f(0);
+  for (int q = 0; q < i - 1; ++q) { f(1); f(0); }
+  int lead = p - i;  // groups of chunk 1 before the alternation starts
+  int turn = 1;
+  while (!(nf[0] == m && nf[1] == m)) {
+    int c;
+    if (lead > 0) { c = 1; --lead; }
+    else { c = turn; turn ^= 1; }
+    f(c); b(c); w(c);
+  }
+}
+
+}  // namespace
+
+zb_status zb_schedule_order_v(int32_t p, int32_t m, zb_op* orders) {
+  if (p < 1 || m < 1 || !orders) return ZB_EINVAL;
+  const size_t n = (size_t)6 * m;
+  std::vector<std::vector<zb_op>> stat(p);
+  for (int s = 0; s < p; ++s) v_static_part(p, s, m, &stat[s]);
+  // final phase: unit pass times, no communication; a free worker runs a ready B (chunk 0 first), else
+  // its oldest pending W (chunk 1 first among equals)
+  std::vector<int> end((size_t)p * 3 * 2 * m, -1);  // [worker][pass][v]
+  auto at = [&](int i, int pass, int v) -> int& { return end[((size_t)i * 3 + pass) * 2 * m + v]; };
+  std::vector<int> len(p, 0), nb((size_t)p * 2, 0), nw((size_t)p * 2, 0);
+  size_t done = 0;
+  for (int t = 0; done < (size_t)p * n; ++t) {
+    if (t > 600 * (m + p)) return ZB_ESTATE;
+    std::vector<zb_op> chosen(p, zb_op{-1, -1});
+    auto ready = [&](int i, int pass, int ch, int k) {
+      const VDep d = v_producer(p, m, i, pass, ch, k);
+      if (d.none) return true;
+      const int e = at(d.worker, d.pass, d.v);
+      return e >= 0 && e <= t;
+    };
+    for (int i = 0; i < p; ++i) {
+      if (len[i] < (int)stat[i].size()) {
+        const zb_op& op = stat[i][len[i]];
+        if (ready(i, op.pass, op.mb / m, op.mb % m)) chosen[i] = op;
+        continue;
+      }
+      for (int ch = 0; ch < 2 && chosen[i].pass < 0; ++ch) {
+        const int k = nb[i * 2 + ch];
+        if (k < m && ready(i, ZB_PASS_B, ch, k)) chosen[i] = zb_op{ZB_PASS_B, ch * m + k};
+      }
+      if (chosen[i].pass < 0) {
+        int best_k = -1, best_ch = -1;
+        for (int ch = 1; ch >= 0; --ch) {
+          const int k = nw[i * 2 + ch];
+          if (k < nb[i * 2 + ch] && (best_ch < 0 || k < best_k)) { best_k = k; best_ch = ch; }
+        }
+        if (best_ch >= 0) chosen[i] = zb_op{ZB_PASS_W, best_ch * m + best_k};
+      }
+    }
+    for (int i = 0; i < p; ++i) {
+      const zb_op& op = chosen[i];
+      if (op.pass < 0) continue;
+      orders[(size_t)i * n + len[i]++] = op;
+      at(i, op.pass, op.mb) = t + 1;
+      ++done;
+      if (op.pass == ZB_PASS_B) nb[i * 2 + op.mb / m] = op.mb % m + 1;
+      else if (op.pass == ZB_PASS_W) nw[i * 2 + op.mb / m] = op.mb % m + 1;
+    }
+  }
+  return ZB_OK;
+}
+
+zb_status zb_simulate_pipeline_v(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times, double* cost,
+                                 double* bubble_rate, double* stage_span) {
+  if (p < 1 || m < 1 || !orders || !valid_times(times)) return ZB_EINVAL;
+  if (!valid_orders(p, 2 * m, orders)) return ZB_EORDER;  // 2m virtual microbatches per worker
+  const Times t{times->t_f, times->t_b, times->t_w, times->t_comm};
+  const size_t n = (size_t)6 * m;
+  std::vector<double> end((size_t)p * n, -1.0), clock(p, 0.0), first(p, 0.0), last(p, 0.0);
+  std::vector<int> ptr(p, 0);
+  auto at = [&](int i, int pass, int v) -> double& { return end[((size_t)i * 3 + pass) * 2 * m + v]; };
+  size_t remaining = (size_t)p * n;
+  while (remaining) {
+    bool progressed = false;
+    for (int i = 0; i < p; ++i) {
+      while (ptr[i] < (int)n) {
+        const zb_op& op = orders[(size_t)i * n + ptr[i]];
+        double ready = clock[i];
+        const VDep d = v_producer(p, m, i, op.pass, op.mb / m, op.mb % m);
+        if (!d.none) {
+          const double e = at(d.worker, d.pass, d.v);
+          if (e < 0) break;
+          const double a = e + (d.link ? t.comm : 0.0);
+          if (a > ready) ready = a;
+        }
+        if (ptr[i] == 0) first[i] = ready;
+        clock[i] = ready + t.of(op.pass);
+        at(i, op.pass, op.mb) = clock[i];
+        last[i] = clock[i];
+        ++ptr[i];
+        --remaining;
+        progressed = true;
+      }
+    }
+    if (!progressed) return ZB_EORDER;
+  }
+  const double c = span_cost(first, last);
+  if (cost) *cost = c;
+  if (bubble_rate) *bubble_rate = (c - 2 * m * (t.f + t.b + t.w)) / c;
+  if (stage_span)
+    for (int i = 0; i < p; ++i) stage_span[i] = last[i] - first[i];
+  return ZB_OK;
+}
+
 zb_status zb_order_memory_peak(const zb_op* ops, int32_t n, double m_b, double m_w, double* peak) {
   if (!ops || n < 0 || !peak) return ZB_EINVAL;
   double cur = 0, top = 0;

@@ -60,6 +60,7 @@ struct zb_stage {
   bool bf16 = true;
   bool group_w = true;
   bool fuse_bw = false;
+  int chunks = 1;  // model chunks held by the stage (2: ZB-V); microbatch indices are then virtual, chunk-major
   int L = 0, h = 0, a = 0, ffn = 0, s = 0, b = 0, T = 0, d = 0;
   size_t esz = 2;
 
@@ -158,6 +159,8 @@ bool valid_shapes(const zb_config* c, std::string* why) {
     return bad("max_microbatches, max_pending_b, max_pending_w, max_inflight must be positive");
   if (c->dtype != ZB_FP32 && c->dtype != ZB_BF16) return bad("dtype must be ZB_FP32 or ZB_BF16");
   if ((long long)c->seq * c->mb_size > (1 << 24)) return bad("too many tokens per microbatch");
+  if (c->chunks != 0 && c->chunks != 1 && c->chunks != 2) return bad("chunks must be 1 or 2");
+  if (c->chunks == 2 && c->layers % 2 != 0) return bad("two chunks need an even number of layers");
   return true;
 }
 
@@ -169,6 +172,7 @@ size_t layout(zb_stage* st, void* arena) {
   st->bf16 = c.dtype == ZB_BF16;
   st->group_w = c.group_w != 0;
   st->fuse_bw = c.fuse_bw != 0;
+  st->chunks = c.chunks == 2 ? 2 : 1;
   st->esz = st->bf16 ? 2 : 4;
   const size_t h = st->h, f = st->ffn, T = st->T;
   const size_t pc[ZB_P_COUNT] = {h, h, h * 3 * h, 3 * h, h * h, h, h, h, h * f, f, f * h, h};
@@ -304,6 +308,15 @@ hipError_t refresh_transposed(zb_stage* st, int l, int i) {
   return launch_transpose_bf16(st->theta16 + off, st->theta16_t + off, rows, cols, st->stream);
 }
 
+// Layers a (virtual) microbatch runs through: all of them, or with two chunks the first half of the stack
+// for virtual microbatches 0 .. m/2-1 (chunk 0) and the second half for m/2 .. m-1 (chunk 1).
+static void layer_range(const zb_stage* st, int mb, int* lo, int* hi) {
+  if (st->chunks == 1) { *lo = 0; *hi = st->L - 1; return; }
+  const int half = st->L / 2;
+  if (mb < st->m / 2) { *lo = 0; *hi = half - 1; }
+  else { *lo = half; *hi = st->L - 1; }
+}
+
 template <typename T> struct Exec {
   // B operand of a dgrad GEMM dIn[T, n_in] = dOut[T, k_out] * W^T with W = [n_in][k_out]
   static void dgrad_weight(zb_stage* st, GemmArgs* g, int l, int wi, int n_in, int k_out) {
@@ -330,13 +343,15 @@ template <typename T> struct Exec {
   }
 
   static zb_status forward(zb_stage* st, int mb) {
-    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    const int h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
     char* fb = st->fb_pool + st->fb_slot * (size_t)st->slot_fb[mb];
     char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
     const T* x = (const T*)(st->in_x + st->act_bytes * (size_t)mb);
     const double E = sizeof(T);
-    for (int l = 0; l < L; ++l) {
+    int l_lo, l_hi;
+    layer_range(st, mb, &l_lo, &l_hi);
+    for (int l = l_lo; l <= l_hi; ++l) {
       const LayerOff& q = st->lo[l];
       T* A = (T*)(fw + q.fw_a);
       T* C = (T*)(fw + q.fw_c);
@@ -348,7 +363,7 @@ template <typename T> struct Exec {
       float* st1 = (float*)(fb + q.fb_stats1);
       float* st2 = (float*)(fb + q.fb_stats2);
       float* lse = (float*)(fb + q.fb_lse);
-      T* y = (l == L - 1) ? (T*)(st->out_y + st->act_bytes * (size_t)mb) : (T*)(fb + st->lo[l + 1].fb_x);
+      T* y = (l == l_hi) ? (T*)(st->out_y + st->act_bytes * (size_t)mb) : (T*)(fb + st->lo[l + 1].fb_x);
       {
         ProfScope ps(st, KC_LN_FWD, 0, 2 * E * T_ * h + 8.0 * T_);
         ZB_HIP(st, launch_layernorm_fwd<T>(x, st->P(l, ZB_P_LN1_G), st->P(l, ZB_P_LN1_B), A, st1, T_, h,
@@ -392,19 +407,21 @@ template <typename T> struct Exec {
 
   // layers l_hi down to l_lo (the whole stack by default)
   static zb_status backward_input(zb_stage* st, int mb, int l_hi = -1, int l_lo = 0) {
-    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    const int h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
     char* fb = st->fb_pool + st->fb_slot * (size_t)st->slot_fb[mb];
     char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
     char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
     T* tmp = (T*)st->tmp;
     const double E = sizeof(T);
-    if (l_hi < 0) l_hi = L - 1;
+    int bottom, top;  // the layers this (virtual) microbatch runs through
+    layer_range(st, mb, &bottom, &top);
+    if (l_hi < 0) { l_hi = top; l_lo = bottom; }
     for (int l = l_hi; l >= l_lo; --l) {
       const LayerOff& q = st->lo[l];
-      // gradient entering layer l: the stage's upstream gradient, or what layer l+1 left in the B->W stash
-      const T* dy = l == L - 1 ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
-      const T* xl = l == 0 ? (const T*)(st->in_x + st->act_bytes * (size_t)mb) : (const T*)(fb + q.fb_x);
+      // gradient entering layer l: the upstream gradient, or what layer l+1 left in the B->W stash
+      const T* dy = l == top ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
+      const T* xl = l == bottom ? (const T*)(st->in_x + st->act_bytes * (size_t)mb) : (const T*)(fb + q.fb_x);
       const T* QKV = (const T*)(fb + q.fb_qkv);
       const T* Y1 = (const T*)(fb + q.fb_y1);
       const T* Fh = (const T*)(fb + q.fb_fh);
@@ -415,7 +432,7 @@ template <typename T> struct Exec {
       T* dQKV = (T*)(bw + q.bw_dqkv);
       T* dY1 = (T*)(bw + q.bw_dy1);
       T* dFh = (T*)(bw + q.bw_dfh);
-      T* dx = l == 0 ? (T*)(st->out_dx + st->act_bytes * (size_t)mb) : (T*)(bw + st->lo[l - 1].bw_dy);
+      T* dx = l == bottom ? (T*)(st->out_dx + st->act_bytes * (size_t)mb) : (T*)(bw + st->lo[l - 1].bw_dy);
 
       GemmArgs g{};  // dFh = (dY W2^T) * gelu'(Fh)
       g.A = dy; g.M = T_; g.N = f; g.K = h;
@@ -459,15 +476,17 @@ template <typename T> struct Exec {
   }
 
   static zb_status backward_weight(zb_stage* st, int mb, int l_hi = -1, int l_lo = 0) {
-    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    const int h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
     char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
     char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
     const double E = sizeof(T);
-    if (l_hi < 0) l_hi = L - 1;
+    int bottom, top;
+    layer_range(st, mb, &bottom, &top);
+    if (l_hi < 0) { l_hi = top; l_lo = bottom; }
     for (int l = l_hi; l >= l_lo; --l) {
       const LayerOff& q = st->lo[l];
-      const T* dyl = l == L - 1 ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
+      const T* dyl = l == top ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
       struct Pair { const T* x; const T* dy; int kin, nout, wi, bi; };
       const Pair pairs[4] = {
           {(const T*)(fw + q.fw_g), dyl, f, h, ZB_P_W2, ZB_P_B2},
@@ -490,7 +509,9 @@ template <typename T> struct Exec {
   // The traditional single backward (Sec. 1): layer by layer, the input gradient and right after it the
   // parameter gradients of the same layer, while that layer's output gradients are still in the caches.
   static zb_status backward_fused(zb_stage* st, int mb) {
-    for (int l = st->L - 1; l >= 0; --l) {
+    int bottom, top;
+    layer_range(st, mb, &bottom, &top);
+    for (int l = top; l >= bottom; --l) {
       zb_status rc = backward_input(st, mb, l, l);
       if (rc != ZB_OK) return rc;
       if ((rc = backward_weight(st, mb, l, l)) != ZB_OK) return rc;
@@ -501,13 +522,15 @@ template <typename T> struct Exec {
   // W of n microbatches (2 <= n <= kGemmGroupMax), parameter by parameter: one grouped wgrad GEMM per
   // weight matrix, then the bias column sums microbatch by microbatch in the same order.
   static zb_status backward_weight_group(zb_stage* st, const int* mbs, int n) {
-    const int L = st->L, h = st->h, f = st->ffn, T_ = st->T;
+    const int h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
     const double E = sizeof(T);
-    for (int l = L - 1; l >= 0; --l) {
+    int bottom, top;  // the same for every member of the group (the caller splits groups at chunk changes)
+    layer_range(st, mbs[0], &bottom, &top);
+    for (int l = top; l >= bottom; --l) {
       const LayerOff& q = st->lo[l];
       struct Lin { size_t fw_off, bw_off; bool top_dy; int kin, nout, wi, bi; };
-      const Lin lins[4] = {{q.fw_g, q.bw_dy, l == L - 1, f, h, ZB_P_W2, ZB_P_B2},
+      const Lin lins[4] = {{q.fw_g, q.bw_dy, l == top, f, h, ZB_P_W2, ZB_P_B2},
                            {q.fw_u, q.bw_dfh, false, h, f, ZB_P_W1, ZB_P_B1},
                            {q.fw_c, q.bw_dy1, false, h, h, ZB_P_WO, ZB_P_BO},
                            {q.fw_a, q.bw_dqkv, false, h, 3 * h, ZB_P_WQKV, ZB_P_BQKV}};
@@ -616,6 +639,7 @@ zb_status zb_config_defaults(zb_config* cfg) {
   cfg->dtype = ZB_BF16;
   cfg->journal = 1;
   cfg->group_w = 1;
+  cfg->chunks = 1;
   cfg->ln_eps = 1e-5f;
   cfg->lr = 1e-4f; cfg->beta1 = 0.9f; cfg->beta2 = 0.95f; cfg->adam_eps = 1e-8f; cfg->weight_decay = 0.01f;
   cfg->clip = 1.0f;
@@ -682,6 +706,8 @@ zb_status zb_begin_iteration(zb_stage* st, int32_t iter, int32_t m) {
   if (!st) return ZB_EINVAL;
   st->err.clear();
   if (m < 1 || m > st->cfg.max_microbatches) return fail(st, ZB_EINVAL, "m must be in [1, max_microbatches]");
+  if (st->chunks == 2 && m % 2 != 0)
+    return fail(st, ZB_EINVAL, "with two chunks m counts virtual microbatches (chunk * m/2 + microbatch): even");
   st->m = m;
   st->iter = iter;
   for (int c = 0; c < 3; ++c) st->done[c].assign(m, 0);
@@ -757,8 +783,16 @@ zb_status zb_backward_weight_group(zb_stage* st, const int32_t* mbs, int32_t n) 
     for (int j = 0; j < i; ++j)
       if (mbs[j] == mbs[i]) return fail(st, ZB_EORDER, "a microbatch appears twice in the group");
   }
-  for (int i0 = 0; i0 < n; i0 += kGemmGroupMax) {  // at most kGemmGroupMax operand pairs per GEMM
-    const int cnt = n - i0 < kGemmGroupMax ? n - i0 : kGemmGroupMax;
+  for (int i0 = 0, cnt = 0; i0 < n; i0 += cnt) {  // at most kGemmGroupMax operand pairs per GEMM, one chunk
+    int lo0, hi0;
+    layer_range(st, mbs[i0], &lo0, &hi0);
+    cnt = 1;
+    while (i0 + cnt < n && cnt < kGemmGroupMax) {
+      int lo1, hi1;
+      layer_range(st, mbs[i0 + cnt], &lo1, &hi1);
+      if (lo1 != lo0) break;
+      ++cnt;
+    }
     zb_status rc;
     if (cnt == 1) rc = st->bf16 ? Exec<bf16_t>::backward_weight(st, mbs[i0]) : Exec<float>::backward_weight(st, mbs[i0]);
     else rc = st->bf16 ? Exec<bf16_t>::backward_weight_group(st, mbs + i0, cnt)
@@ -1004,7 +1038,7 @@ zb_status zb_stage_model_flops(const zb_stage* st, int32_t m, double* flops) {
   if (!st || !flops || m < 0) return ZB_EINVAL;
   const double s = st->s, b = st->b, h = st->h;
   const double F = s * b * h * (24 * h + 4 * s), B = s * b * h * (24 * h + 8 * s), W = s * b * h * 24 * h;
-  *flops = (double)st->L * m * (F + B + W);
+  *flops = (double)(st->L / st->chunks) * m * (F + B + W);  // with two chunks m counts virtual microbatches
   return ZB_OK;
 }
 

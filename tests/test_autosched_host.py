@@ -94,3 +94,22 @@ def test_argument_checks():
         zb.auto_schedule(2, 2, 1.0, 1.0, 1.0, 0.0, 2.0, 1.0, 1.5)      # M_W above M_B
     with pytest.raises(zb.ZbError):
         zb.auto_schedule(0, 2, 1.0, 1.0, 1.0, 0.0, 2.0, 1.0, 0.5)
+
+
+@pytest.mark.parametrize("p,m", [(1, 3), (2, 3), (3, 7), (4, 8), (8, 24), (16, 48), (5, 6), (32, 96)])
+def test_zbv_orders_and_timing_match_oracle(p, m):
+    from oracle import zbv as V
+    got = zb.schedule_order_v(p, m)
+    o = V.orders_v(p, m)
+    assert got == [[(c, ch * m + k) for c, ch, k in ops] for ops in o]
+    for times in ((1.0, 1.0, 1.0, 0.0), (1.0, 1.1, 0.8, 0.05)):
+        cost, rate, spans = zb.simulate_pipeline_v(got, m, *times)
+        start, end = V.simulate_v(o, *times)
+        want = [max(end[i].values()) - min(start[i].values()) for i in range(p)]
+        assert spans == want and cost == max(want)
+        assert rate == (cost - 2 * m * (times[0] + times[1] + times[2])) / cost
+    if m >= 2 * p - 1:
+        assert zb.simulate_pipeline_v(got, m, 1.0, 1.0, 1.0)[1] == 0.0      # Sec. 6: zero bubble
+    for ops in got:                                                        # 2p chunk activations = p M_B
+        assert zb.order_memory_peak(ops, 0.5, 0.5) <= p
+        assert zb.order_stash_need(ops)[2] <= 2 * p

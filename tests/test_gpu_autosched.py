@@ -68,3 +68,57 @@ def test_run_order_checks_its_argument_and_the_pools():
         dev.run_order(two_in_flight)                            # second F finds no free slot
     assert e.value.status == zb.ENOMEM
     dev.close()
+
+
+def test_zbv_order_on_a_two_chunk_stage():
+    # Sec. 6: the stage holds two chunks (here one layer each); worker 2 of 4 runs its ZB-V order over
+    # 2m virtual microbatches.  Each chunk is checked against an oracle stage made of that chunk's layers.
+    import paper_2401_10241_amd as zb
+    from oracle import zbv as V
+    p, sigma, m = 4, 1, 8
+    w = W("zbv", "bf16", 2, 256, 4, 1024, 128, 1, p, sigma, 2 * m, "H1", seed=37)
+    ops = zb.schedule_order_v(p, m)[sigma]
+    assert ops == [(c, ch * m + k) for c, ch, k in V.orders_v(p, m)[sigma]]
+    pools = zb.order_stash_need(ops)
+    assert pools[2] <= 2 * p
+    params = zb_inputs.stage_params(w)
+    dev = zb.Stage(layers=2, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, dtype="bf16", chunks=2,
+                   max_microbatches=2 * m, max_pending_b=pools[0], max_pending_w=pools[1], max_inflight=pools[2])
+    dev.set_params(params)
+    dev.begin_iteration(0, 2 * m)
+    load_iteration(w, 0, 2 * m, dev)
+    dev.run_order(ops)
+    dev.synchronize()
+    grads = dev.get_group(zb.T_GRAD)
+    w1 = w.scaled(layers=1, m=m)
+    worst = 0.0
+    from zb_testlib import rel_fro
+    from oracle.stage import PARAM_ORDER
+    for ch in (0, 1):
+        orc = make_oracle(w1, params[ch:ch + 1])
+        orc.begin_iteration(m)
+        for k in range(m):
+            orc.set_input(k, zb_inputs.stage_input(w, 0, ch * m + k))
+            orc.set_upstream_grad(k, zb_inputs.upstream_grad(w, 0, ch * m + k))
+        orc.run([(c, v - ch * m) for c, v in ops if v // m == ch])
+        for k in range(m):
+            e1 = rel_fro(dev.get_tensor(zb.T_OUTPUT_Y, 0, ch * m + k), orc.Y[k])
+            e2 = rel_fro(dev.get_tensor(zb.T_OUTPUT_DX, 0, ch * m + k), orc.dX[k])
+            assert e1 <= TOL["bf16"] and e2 <= TOL["bf16"], (ch, k, e1, e2)
+            worst = max(worst, e1, e2)
+        for name in PARAM_ORDER:
+            e = rel_fro(grads[ch][name], orc.grads[0][name])
+            assert e <= TOL["bf16"], (ch, name, e)
+            worst = max(worst, e)
+    zbv_grads = dev.get_tensor(zb.T_FLAT_GRADS).copy()
+    # any other legal order of the same virtual microbatches gives the same bits
+    dev.begin_iteration(1, 2 * m)
+    for v in range(2 * m):
+        dev.forward(v)
+        dev.backward_input(v)
+        dev.backward_weight(v)
+    dev.synchronize()
+    assert dev.get_tensor(zb.T_FLAT_GRADS).tobytes() == zbv_grads.tobytes()
+    with pytest.raises(zb.ZbError):
+        dev.begin_iteration(2, 2 * m - 1)      # virtual microbatch count must be even
+    dev.close()
