@@ -1,5 +1,5 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
-Tolerances are the spec ones: max relative Frobenius error 1e-4 (fp32), 2e-2 (bf16);
+Tolerances: max relative Frobenius error 1e-4 (fp32), 2e-2 (bf16);
 schedule order, rollback and accumulation determinism are bit-exact."""
 import numpy as np
 import pytest
@@ -37,7 +37,7 @@ def run_and_compare(w, m=None, mbs_full=None):
 
 
 def test_c1_tiny_fp32_full():
-    # BASELINE config 1: stage 0 of p=4, ZB-H1, m=8, fp32
+    # workload c1: stage 0 of p=4, ZB-H1, m=8, fp32
     run_and_compare(zb_inputs.workload("c1"))
 
 

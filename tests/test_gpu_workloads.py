@@ -1,4 +1,4 @@
-"""GPU parity at the BASELINE workloads' full shapes (c2..c5), in the launch configuration bench.py
+"""GPU parity at the full shapes of workloads c2..c5, in the launch configuration bench.py
 times (full m, the workload's schedule kind, p and stage).
 
 The fp64 oracle needs ~10 s of host time per microbatch at these sizes, so it is run on SAMPLED
@@ -203,7 +203,7 @@ def test_c5_full_shapes_rollback_identity():
 @pytest.mark.parametrize("name,h,a,ffn,b", [("1.5B-b6", 2304, 24, 9216, 6), ("6.2B-b3", 4096, 32, 16384, 3)])
 def test_papers_microbatch_sizes(name, h, a, ffn, b):
     # Sec. 5.1's table runs the 1.5B model with 6 and the 6.2B model with 3 sequences per microbatch
-    # (BASELINE's c2 / c3 use 1): one layer, two microbatches of that size, every tensor against the oracle
+    # (workloads c2 / c3 use 1): one layer, two microbatches of that size, every tensor against the oracle
     from zb_testlib import compare_outputs, load_iteration
     w = zb_inputs.Workload(name, "bf16", 1, h, a, ffn, 1024, b, 8, 4, 2, "H1", seed=41)
     params = zb_inputs.stage_params(w)

@@ -6,7 +6,7 @@ import zb_inputs
 from oracle import optimizer as O
 from oracle.stage import StageOracle, PARAM_ORDER
 
-TOL = {"fp32": 1e-4, "bf16": 2e-2}   # max relative Frobenius error (spec tolerances)
+TOL = {"fp32": 1e-4, "bf16": 2e-2}   # max relative Frobenius error per tensor: fp32 arithmetic, bf16 storage with fp32 accumulation
 
 
 def rel_fro(a, b):
