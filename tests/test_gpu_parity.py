@@ -348,3 +348,23 @@ def test_algorithm_1_rollback_without_journal_is_close_but_not_exact():
     assert rel_fro(after[1], before[1]) < 1e-4
     assert rel_fro(after[2], before[2]) < 1e-4
     dev.close()
+
+
+SWEEP = [
+    # hidden, heads, ffn, seq, b, layers, dtype      which kernels the shape reaches
+    (128, 2, 512, 64, 2, 2, "bf16"),      # head size 64, N = 384 / 128 not multiples of 256: generic GEMMs
+    (512, 4, 2048, 256, 1, 2, "bf16"),    # head size 128, every GEMM on the MFMA kernel, 256-token tiles
+    (768, 12, 3072, 128, 3, 1, "bf16"),   # head size 64, 384 tokens: 128-row tiles only
+    (320, 4, 1280, 96, 1, 2, "bf16"),     # head size 80 and 96 tokens: generic attention, mixed GEMMs
+    (1024, 8, 4096, 200, 1, 1, "bf16"),   # head size 128 but a ragged sequence: generic attention, 200-token GEMMs
+    (384, 4, 1536, 192, 2, 1, "bf16"),    # head size 96
+    (256, 2, 1024, 320, 1, 1, "fp32"),    # fp32 arithmetic everywhere
+    (2048, 16, 8192, 512, 1, 1, "bf16"),  # split-K shapes with 512 tokens
+]
+
+
+@pytest.mark.parametrize("cfg", SWEEP, ids=lambda c: "h%d_a%d_f%d_s%d_b%d_L%d_%s" % c)
+def test_shape_sweep(cfg):
+    hidden, heads, ffn, seq, b, layers, dtype = cfg
+    w = W("sweep", dtype, layers, hidden, heads, ffn, seq, b, 4, 1, 3, "H2", seed=101 + hidden + seq)
+    run_and_compare(w)
