@@ -29,15 +29,8 @@
 // starting at 8 * (l >> 5); it receives column (l & 31) and rows 8*(v/4) + 4*(l >> 5) + v%4 of the
 // 32 x 32 result in accumulator element v.
 #include <type_traits>
-#include <cstdlib>
 
 #include "gemm_epilogue.h"
-#ifndef ZB_DIAG_MFMA
-#define ZB_DIAG_MFMA(x) x
-#endif
-#ifndef ZB_DIAG_EPI
-#define ZB_DIAG_EPI(x) x
-#endif
 
 namespace zb {
 
@@ -216,7 +209,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
     for (int i = 0; i < MT; ++i)
 #pragma unroll
       for (int j = 0; j < NT; ++j)
-        ZB_DIAG_MFMA(acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0));
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
   };
   auto step = [&](int it, auto parity_tag) {
     constexpr int parity = decltype(parity_tag)::value;
@@ -256,7 +249,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-      ZB_DIAG_EPI((epilogue_tile<bf16_t, MODE>(epi, m0 + wm + i * 32 + lhi, n0 + wn + j * 32 + lrow, acc[i][j])));
+      epilogue_tile<bf16_t, MODE>(epi, m0 + wm + i * 32 + lhi, n0 + wn + j * 32 + lrow, acc[i][j]);
     }
 }
 
