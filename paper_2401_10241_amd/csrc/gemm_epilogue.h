@@ -43,7 +43,8 @@ __device__ __forceinline__ void epilogue_one(const EpiParams& e, int m, int n, f
 
 // One 32 x 32 MFMA accumulator tile: lane holds column n and the 16 rows m0 + 8*(v/4) + (v%4), v = 0..15
 // (m0 already includes the lane's 4*(lane>>5) offset).  All reads of the tile are issued before any
-// write, so the loads overlap instead of each waiting for the previous store.
+// write, so the loads overlap instead of each waiting for the previous store.  (The fp32 accumulate of
+// the wgrad GEMM is not an epilogue in the MFMA path: its kernel starts the accumulators from C.)
 template <typename T, int MODE>
 __device__ __forceinline__ void epilogue_tile(const EpiParams& e, int m0, int n, const f32x16& acc) {
   size_t idx[16];
@@ -52,12 +53,6 @@ __device__ __forceinline__ void epilogue_tile(const EpiParams& e, int m0, int n,
   if (MODE == EPI_PARTIAL) {  // e.outf already points at this K slice's [M,N] plane
 #pragma unroll
     for (int v = 0; v < 16; ++v) e.outf[idx[v]] = acc[v];
-  } else if (MODE == EPI_ACCUM_F32) {
-    float c[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) c[v] = e.outf[idx[v]];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) e.outf[idx[v]] = c[v] + acc[v];
   } else if (MODE == EPI_BIAS_RESID || MODE == EPI_DGELU) {
     float a[16];
 #pragma unroll

@@ -5,6 +5,8 @@
 //   GEMM) and A either K-contiguous ([m][k]: activations in forward / dgrad) or row-contiguous ([k][m]:
 //   the stashed layer input in wgrad).
 //
+// The wgrad GEMM (both operands row-contiguous, fp32 accumulate into C) has a kernel of its own below.
+//
 // One 512-thread workgroup (8 wavefronts, 2 x 4) owns a BM x 256 output tile (BM = 256 or 128) and walks K
 // in steps of 32.  Tiles travel global memory -> LDS directly (global_load_lds_dwordx4: each lane's 16
 // bytes land at consecutive LDS addresses, no registers in between) into rings of LDS stages, several
@@ -118,12 +120,12 @@ template <int BM, int BS, bool ATR> struct Cfg {
   }
 };
 
-template <int BM, int BS, bool ATR, int MODE>
+template <int BM, int BS, int MODE>
 __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ B, int M, int N, int K,
                                                             long lda, long ldb, EpiParams epi, int ksplit) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  typedef Cfg<BM, BS, ATR> C;
+  typedef Cfg<BM, BS, false> C;
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
   bf16_t* sB = sA + C::A_STAGES * C::A_ELEMS;
   constexpr int WM = BM / 2;
@@ -175,17 +177,12 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   // refills issued by step `it` (also used, with negative it, for the pipeline fill so that the order of
   // loads is the same from the first step on)
   auto issue = [&](int it) {
-    if constexpr (!ATR) {
-      if ((it & 1) == 0) {
-        const int j = (it >> 1) + 1;  // A tile j covers steps 2j, 2j+1 (j = -1 during the fill: nothing)
-        if (j >= 0 && 2 * j < nk) dma_rows<BM>(A, lda, m0, j * 64, sA + (j & 1) * C::A_ELEMS, wave, lane);
-      }
+    if ((it & 1) == 0) {
+      const int j = (it >> 1) + 1;  // A tile j covers steps 2j, 2j+1 (j = -1 during the fill: nothing)
+      if (j >= 0 && 2 * j < nk) dma_rows<BM>(A, lda, m0, j * 64, sA + (j & 1) * C::A_ELEMS, wave, lane);
     }
     const int nt = it + BS - 1;
-    if (nt < nk) {
-      if constexpr (ATR) dma_tr<BM>(A, lda, m0, nt * KS, sA + (nt % BS) * C::A_ELEMS, wave, lane);
-      dma_tr<BN>(B, ldb, n0, nt * KS, sB + (nt % BS) * C::B_ELEMS, wave, lane);
-    }
+    if (nt < nk) dma_tr<BN>(B, ldb, n0, nt * KS, sB + (nt % BS) * C::B_ELEMS, wave, lane);
   };
   // With one workgroup per CU (BS > 3) the MFMAs of the second half of every tile are issued after the
   // NEXT step's barrier: a wave then reaches the barrier with matrix work still queued, and the matrix
@@ -195,12 +192,9 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   bf16x8 af1[MT], bf1[NT];  // fragments of the current tile's second half, kept across the barrier
   auto load_frags = [&](int it, int parity, int kk, bf16x8 (&af)[MT], bf16x8 (&bfr)[NT]) {
     const bf16_t* b_s = sB + (it % BS) * C::B_ELEMS;
-    const bf16_t* a_s = ATR ? sA + (it % BS) * C::A_ELEMS : sA + ((it >> 1) & 1) * C::A_ELEMS;
+    const bf16_t* a_s = sA + ((it >> 1) & 1) * C::A_ELEMS;
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      if constexpr (ATR) af[i] = frag_tr<BM>(a_s, wm + i * 32, kk, lane);
-      else af[i] = frag_rows(a_s, wm + i * 32, parity * 2 + kk, lane);
-    }
+    for (int i = 0; i < MT; ++i) af[i] = frag_rows(a_s, wm + i * 32, parity * 2 + kk, lane);
 #pragma unroll
     for (int j = 0; j < NT; ++j) bfr[j] = frag_tr<BN>(b_s, wn + j * 32, kk, lane);
   };
@@ -254,10 +248,10 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
 }
 
 // ldo: row stride of the outputs when the GEMM covers a column range of a wider matrix (0: g.N)
-template <int BM, int BS, bool ATR, int MODE>
+template <int BM, int BS, int MODE>
 hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s, int ksplit = 1, int ldo = 0) {
-  auto kern = gemm_mfma_kernel<BM, BS, ATR, MODE>;
-  constexpr size_t smem = Cfg<BM, BS, ATR>::SMEM;
+  auto kern = gemm_mfma_kernel<BM, BS, MODE>;
+  constexpr size_t smem = Cfg<BM, BS, false>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool attr_set = false;  // one device per process in this library
   if (!attr_set) {
@@ -314,20 +308,23 @@ __global__ __launch_bounds__(256) void gemm_splitk_fixup_kernel(const float* __r
   *reinterpret_cast<bf16x4*>((bf16_t*)epi.out0 + i4) = o0;
 }
 
-// Grouped wgrad: C += A_0^T B_0, then += A_1^T B_1, ... for `ngroup` operand pairs of one shape (the W
-// passes of consecutive microbatches).  The old C is read once, when the kernel starts, and the new C is
-// written once; the ring of LDS stages runs on across the pairs without draining.  Each pair's product is
-// accumulated from zero and added to the running C in fp32, so the result has exactly the bits of
-// `ngroup` separate accumulate launches.  128 x 256 tile (64 accumulator + 64 running-C registers per lane:
-// eight wavefronts at two per SIMD have 256 registers each), one workgroup per CU, five-stage ring.
+// wgrad: C += A_0^T B_0 + A_1^T B_1 + ... for `ngroup` >= 1 operand pairs of one shape (the W passes of one
+// or of several consecutive microbatches), both operands row-contiguous ([k][m], [k][n]).  The accumulators
+// START from the old C (requested before anything else, so the read travels while the ring of LDS stages
+// fills) and every MFMA adds into them, pair after pair, in k order; the new C is written once at the end
+// and nothing is read back there.  An element's value is therefore the same chain of fp32 MFMA additions
+// whatever the tile shape, ring depth or grouping: `ngroup` pairs in one launch give exactly the bits of
+// `ngroup` launches of one pair.  The ring runs on across the pairs without draining.
 struct GroupPtrs {
   const bf16_t* a[kGemmGroupMax];
   const bf16_t* b[kGemmGroupMax];
 };
 
-template <int BM, int BS>
-__global__ __launch_bounds__(512, 2) void gemm_wgrad_group_kernel(GroupPtrs gp, int ngroup, int M, int N, int Kc,
-                                                                  long lda, long ldb, float* __restrict__ outf) {
+template <int BM, int BS, bool XB>
+__global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgrad_kernel(GroupPtrs gp, int ngroup,
+                                                                                       int M, int N, int Kc, long lda,
+                                                                                       long ldb,
+                                                                                       float* __restrict__ outf) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   typedef Cfg<BM, BS, true> C;
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
@@ -350,22 +347,18 @@ __global__ __launch_bounds__(512, 2) void gemm_wgrad_group_kernel(GroupPtrs gp, 
   const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
   const int lrow = lane & 31, lhi = (lane >> 5) * 4;
 
-  // running C: the old values, requested before anything else so that they arrive behind the first tiles
-  f32x16 c[MT][NT], acc[MT][NT];
+  f32x16 acc[MT][NT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const float* p0 = outf + (size_t)(m0 + wm + i * 32 + lhi) * N + n0 + wn + j * 32 + lrow;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        c[i][j][v] = p0[(size_t)((v >> 2) * 8 + (v & 3)) * N];
-        acc[i][j][v] = 0.f;
-      }
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = p0[(size_t)((v >> 2) * 8 + (v & 3)) * N];
       __builtin_amdgcn_sched_barrier(0);  // one tile's addresses at a time
     }
 
-  const int spc = Kc / KS;        // steps per operand pair (even)
+  const int spc = Kc / KS;        // steps per operand pair
   const int nk = ngroup * spc;
   int g_next = 0, k_next = 0;  // operand pair and k offset of the next tile to fetch (tiles are fetched in order)
   auto issue = [&](int it) {
@@ -377,7 +370,7 @@ __global__ __launch_bounds__(512, 2) void gemm_wgrad_group_kernel(GroupPtrs gp, 
       if (k_next == Kc) { k_next = 0; ++g_next; }
     }
   };
-  bf16x8 af1[MT], bf1[NT];  // fragments of a tile's second half, carried across the next barrier
+  bf16x8 af1[MT], bf1[NT];  // XB: fragments of a tile's second half, carried across the next barrier
   auto load_frags = [&](int it, int kk, bf16x8 (&af)[MT], bf16x8 (&bfr)[NT]) {
     const bf16_t* a_s = sA + (it % BS) * C::A_ELEMS;
     const bf16_t* b_s = sB + (it % BS) * C::B_ELEMS;
@@ -392,41 +385,35 @@ __global__ __launch_bounds__(512, 2) void gemm_wgrad_group_kernel(GroupPtrs gp, 
 #pragma unroll
       for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
   };
-  auto fold = [&]() {  // one operand pair is complete: add its product to the running C, start the next from zero
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          c[i][j][v] += acc[i][j][v];
-          acc[i][j][v] = 0.f;
-        }
-  };
 
 #pragma unroll
   for (int it = 1 - BS; it < 0; ++it) issue(it);
-  int until_fold = spc;
   for (int it = 0; it < nk; ++it) {
     if (it + BS - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::allowed(0)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
     bf16x8 af0[MT], bf0[NT];
-    load_frags(it, 0, af0, bf0);
-    if (it > 0) {
-      mfmas(af1, bf1);  // second half of step it-1, issued after this step's barrier
-      if (--until_fold == 0) { fold(); until_fold = spc; }
+    if constexpr (XB) {
+      // the MFMAs of a step's second half are issued after the next step's barrier (one workgroup per CU:
+      // the matrix pipe keeps work queued while the waves re-synchronise)
+      load_frags(it, 0, af0, bf0);
+      if (it > 0) mfmas(af1, bf1);
+      mfmas(af0, bf0);
+      load_frags(it, 1, af1, bf1);
+      issue(it);
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragment reads done before the next barrier
+    } else {
+      issue(it);
+      load_frags(it, 0, af0, bf0);
+      mfmas(af0, bf0);
+      load_frags(it, 1, af1, bf1);
+      mfmas(af1, bf1);
     }
-    mfmas(af0, bf0);
-    load_frags(it, 1, af1, bf1);
-    issue(it);
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragment reads done before the next barrier
   }
-  mfmas(af1, bf1);
-  fold();
+  if constexpr (XB) mfmas(af1, bf1);
 
   // the store addresses are worked out again here (from a copy of the tile origin the compiler cannot
-  // connect with the one used for the loads), or 64 address pairs would stay in registers across the loop
+  // connect with the one used for the loads), or the address pairs would stay in registers across the loop
   int m0s = m0, n0s = n0;
   asm volatile("" : "+s"(m0s), "+s"(n0s));
 #pragma unroll
@@ -435,7 +422,7 @@ __global__ __launch_bounds__(512, 2) void gemm_wgrad_group_kernel(GroupPtrs gp, 
     for (int j = 0; j < NT; ++j) {
       float* p0 = outf + (size_t)(m0s + wm + i * 32 + lhi) * N + n0s + wn + j * 32 + lrow;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) p0[(size_t)((v >> 2) * 8 + (v & 3)) * N] = c[i][j][v];
+      for (int v = 0; v < 16; ++v) p0[(size_t)((v >> 2) * 8 + (v & 3)) * N] = acc[i][j][v];
       __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -454,7 +441,7 @@ bool try_split_k(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipError_
   GemmArgs p = g;
   p.epilogue = EPI_PARTIAL;
   p.outf = g.workspace;
-  *err = run_cfg<256, 5, false, EPI_PARTIAL>(p, lda, ldb, s, slices);
+  *err = run_cfg<256, 5, EPI_PARTIAL>(p, lda, ldb, s, slices);
   if (*err != hipSuccess) return true;
   const size_t threads = plane / 4;
   gemm_splitk_fixup_kernel<MODE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(g.workspace, slices, plane, g.N,
@@ -481,7 +468,7 @@ bool try_tail_split(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipErr
   if ((size_t)slices * plane > g.workspace_floats) return false;
   GemmArgs a = g;
   a.N = n_main;
-  *err = run_cfg<256, 5, false, MODE>(a, lda, ldb, s, 1, g.N);
+  *err = run_cfg<256, 5, MODE>(a, lda, ldb, s, 1, g.N);
   if (*err != hipSuccess) return true;
   GemmArgs t = g;  // the same GEMM on columns n_main .. N-1
   t.N = n_tail;
@@ -493,7 +480,7 @@ bool try_tail_split(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipErr
   GemmArgs p = t;
   p.epilogue = EPI_PARTIAL;
   p.outf = g.workspace;
-  *err = run_cfg<256, 5, false, EPI_PARTIAL>(p, lda, ldb, s, slices);
+  *err = run_cfg<256, 5, EPI_PARTIAL>(p, lda, ldb, s, slices);
   if (*err != hipSuccess) return true;
   EpiParams epi = make_epi(t);
   epi.N = g.N;
@@ -504,14 +491,12 @@ bool try_tail_split(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipErr
   return true;
 }
 
-template <bool ATR, int MODE>
+template <int MODE>
 hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool* taken) {
   *taken = true;
-  if constexpr (!ATR) {
-    hipError_t e = hipSuccess;
-    if (try_split_k<MODE>(g, lda, ldb, s, &e)) return e;
-    if (try_tail_split<MODE>(g, lda, ldb, s, &e)) return e;
-  }
+  hipError_t e = hipSuccess;
+  if (try_split_k<MODE>(g, lda, ldb, s, &e)) return e;
+  if (try_tail_split<MODE>(g, lda, ldb, s, &e)) return e;
   if (g.N % BN == 0) {
     // Rounds of tiles over the 256 CUs times the tile height; the taller tile does about 1.25x the
     // work per cycle, so it wins only when it does not cost an extra, mostly empty round.
@@ -519,13 +504,13 @@ hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool*
     const long t128 = g.M % 128 == 0 ? (long)(g.M / 128) * (g.N / BN) : 0;
     const double c256 = t256 ? (double)((t256 + 255) / 256) * 256.0 / 1.25 : 1e30;
     const double c128 = t128 ? (double)((t128 + 255) / 256) * 128.0 : 1e30;
-    if (t256 && c256 <= c128 && MODE != EPI_ACCUM_F32) return run_cfg<256, ATR ? 4 : 5, ATR, MODE>(g, lda, ldb, s);
+    if (t256 && c256 <= c128) return run_cfg<256, 5, MODE>(g, lda, ldb, s);
     if (t128) {
       // more tiles than CUs: a three-stage ring (<= 80 KB) lets two workgroups share a CU, so one's
       // epilogue and pipeline fill hide behind the other's MFMAs; otherwise one workgroup per CU with a
       // deeper ring
-      if (t128 > 256) return run_cfg<128, 3, ATR, MODE>(g, lda, ldb, s);
-      return run_cfg<128, 5, ATR, MODE>(g, lda, ldb, s);
+      if (t128 > 256) return run_cfg<128, 3, MODE>(g, lda, ldb, s);
+      return run_cfg<128, 5, MODE>(g, lda, ldb, s);
     }
   }
   *taken = false;
@@ -541,21 +526,9 @@ template <typename T> hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t
   return hipSuccess;
 }
 
-// grouped wgrad launch; *taken stays false if the shape is not one for the grouped kernel
-static hipError_t launch_wgrad_group(const GemmArgs& g, hipStream_t s, bool* taken) {
-  constexpr int BM = 128, BS = 5;
-  // below four pairs the lone workgroup per CU loses more in the main loop than it saves in epilogues
-  if (g.epilogue != EPI_ACCUM_F32 || g.group < 4 || g.group > kGemmGroupMax) return hipSuccess;
-  if (!(g.a_sm == 1 && g.b_sn == 1) || g.a_sk != g.M || g.b_sk != g.N) return hipSuccess;
-  if (g.M % BM != 0 || g.N % BN != 0 || g.K % 64 != 0 || !aligned16(g.outf)) return hipSuccess;
-  if ((long)g.M * g.N >= (1L << 31)) return hipSuccess;
-  GroupPtrs gp;
-  for (int i = 0; i < kGemmGroupMax; ++i) {
-    gp.a[i] = (const bf16_t*)g.group_a[i < g.group ? i : 0];
-    gp.b[i] = (const bf16_t*)g.group_b[i < g.group ? i : 0];
-    if (!gp.a[i] || !gp.b[i] || !aligned16(gp.a[i]) || !aligned16(gp.b[i])) return hipSuccess;
-  }
-  auto kern = gemm_wgrad_group_kernel<BM, BS>;
+template <int BM, int BS, bool XB>
+hipError_t run_wgrad(const GroupPtrs& gp, const GemmArgs& g, int ngroup, long lda, long ldb, hipStream_t s) {
+  auto kern = gemm_wgrad_kernel<BM, BS, XB>;
   constexpr size_t smem = Cfg<BM, BS, true>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
@@ -565,28 +538,48 @@ static hipError_t launch_wgrad_group(const GemmArgs& g, hipStream_t s, bool* tak
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  *taken = true;
   const int grid = (g.M / BM) * (g.N / BN);
-  kern<<<grid, NTHREADS, smem, s>>>(gp, g.group, g.M, g.N, g.K, (long)g.a_sk, (long)g.b_sk, g.outf);
+  kern<<<grid, NTHREADS, smem, s>>>(gp, ngroup, g.M, g.N, g.K, lda, ldb, g.outf);
   return hipGetLastError();
+}
+
+// wgrad launch (one pair, or g.group pairs); *taken stays false if the shape is not one for the MFMA kernel
+static hipError_t launch_wgrad(const GemmArgs& g, hipStream_t s, bool* taken) {
+  const int ngroup = g.group >= 2 ? g.group : 1;
+  if (g.epilogue != EPI_ACCUM_F32 || ngroup > kGemmGroupMax) return hipSuccess;
+  if (!(g.a_sm == 1 && g.b_sn == 1) || g.a_sk == 1 || g.b_sk == 1) return hipSuccess;
+  const long lda = g.a_sk, ldb = g.b_sk;
+  if (g.M % 128 != 0 || g.N % BN != 0 || g.K % 64 != 0 || lda % 8 != 0 || ldb % 8 != 0 || !aligned16(g.outf))
+    return hipSuccess;
+  GroupPtrs gp;
+  for (int i = 0; i < kGemmGroupMax; ++i) {
+    gp.a[i] = (const bf16_t*)(g.group >= 2 ? g.group_a[i < ngroup ? i : 0] : g.A);
+    gp.b[i] = (const bf16_t*)(g.group >= 2 ? g.group_b[i < ngroup ? i : 0] : g.B);
+    if (!gp.a[i] || !gp.b[i] || !aligned16(gp.a[i]) || !aligned16(gp.b[i])) return hipSuccess;
+  }
+  *taken = true;
+  // 256-row tiles (one workgroup per CU, four-stage ring) when they fill most of the chip; else 128-row
+  // tiles, two workgroups per CU with a three-stage ring if there are more tiles than CUs, one with a
+  // five-stage ring otherwise.  The choice does not change the result (see the kernel).
+  const long t256 = g.M % 256 == 0 ? (long)(g.M / 256) * (g.N / BN) : 0;
+  const long t128 = (long)(g.M / 128) * (g.N / BN);
+  if (t256 >= 192) return run_wgrad<256, 4, true>(gp, g, ngroup, lda, ldb, s);
+  if (t128 > 256) return run_wgrad<128, 3, true>(gp, g, ngroup, lda, ldb, s);
+  return run_wgrad<128, 5, true>(gp, g, ngroup, lda, ldb, s);
 }
 
 template <> hipError_t launch_gemm_mfma<bf16_t>(const GemmArgs& g, hipStream_t s, bool* taken) {
   *taken = false;
-  if (g.group >= 2) return launch_wgrad_group(g, s, taken);
-  const bool atr = g.a_sm == 1 && g.a_sk != 1, btr = g.b_sn == 1 && g.b_sk != 1;
-  if (!btr) return hipSuccess;  // B must be row-contiguous
-  const long lda = atr ? g.a_sk : g.a_sm, ldb = g.b_sk;
+  if (g.epilogue == EPI_ACCUM_F32) return launch_wgrad(g, s, taken);
+  // forward X[M,K] * W[K,N]; dgrad dY[M,K'] * Wt[K',N']: A K-contiguous, B row-contiguous
+  if (g.a_sk != 1 || !(g.b_sn == 1 && g.b_sk != 1)) return hipSuccess;
+  const long lda = g.a_sm, ldb = g.b_sk;
   if (g.K % 64 != 0 || lda % 8 != 0 || ldb % 8 != 0 || !aligned16(g.A) || !aligned16(g.B)) return hipSuccess;
-  if (!atr) {  // forward X[M,K] * W[K,N]; dgrad dY[M,K'] * Wt[K',N']
-    if (g.epilogue == EPI_BIAS) return run_shape<false, EPI_BIAS>(g, lda, ldb, s, taken);
-    if (g.epilogue == EPI_BIAS_RESID) return run_shape<false, EPI_BIAS_RESID>(g, lda, ldb, s, taken);
-    if (g.epilogue == EPI_BIAS_GELU) return run_shape<false, EPI_BIAS_GELU>(g, lda, ldb, s, taken);
-    if (g.epilogue == EPI_STORE) return run_shape<false, EPI_STORE>(g, lda, ldb, s, taken);
-    if (g.epilogue == EPI_DGELU) return run_shape<false, EPI_DGELU>(g, lda, ldb, s, taken);
-  } else {  // wgrad: X[K,M]^T * dY[K,N]
-    if (g.epilogue == EPI_ACCUM_F32) return run_shape<true, EPI_ACCUM_F32>(g, lda, ldb, s, taken);
-  }
+  if (g.epilogue == EPI_BIAS) return run_shape<EPI_BIAS>(g, lda, ldb, s, taken);
+  if (g.epilogue == EPI_BIAS_RESID) return run_shape<EPI_BIAS_RESID>(g, lda, ldb, s, taken);
+  if (g.epilogue == EPI_BIAS_GELU) return run_shape<EPI_BIAS_GELU>(g, lda, ldb, s, taken);
+  if (g.epilogue == EPI_STORE) return run_shape<EPI_STORE>(g, lda, ldb, s, taken);
+  if (g.epilogue == EPI_DGELU) return run_shape<EPI_DGELU>(g, lda, ldb, s, taken);
   return hipSuccess;
 }
 
