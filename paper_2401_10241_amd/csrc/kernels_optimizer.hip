@@ -13,6 +13,8 @@ __device__ __forceinline__ int nonfinite_bits(float v) {
   return (__float_as_uint(v) & 0x7F800000u) == 0x7F800000u ? 1 : 0;
 }
 
+// Level 1: one 16-byte element per thread (workgroups in index order sweep the gradient as one moving
+// front), one partial sum and one non-finite flag per workgroup.
 __global__ __launch_bounds__(256) void grad_sumsq_kernel(const float4* __restrict__ g, size_t n4,
                                                          double* __restrict__ partial_sq,
                                                          int* __restrict__ partial_nf) {
@@ -20,11 +22,11 @@ __global__ __launch_bounds__(256) void grad_sumsq_kernel(const float4* __restric
   __shared__ int redf[4];
   double acc = 0.0;
   int bad = 0;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) {
     const float4 v = g[i];
-    bad |= nonfinite_bits(v.x) | nonfinite_bits(v.y) | nonfinite_bits(v.z) | nonfinite_bits(v.w);
-    acc += ((double)v.x * v.x + (double)v.y * v.y) + ((double)v.z * v.z + (double)v.w * v.w);
+    bad = nonfinite_bits(v.x) | nonfinite_bits(v.y) | nonfinite_bits(v.z) | nonfinite_bits(v.w);
+    acc = ((double)v.x * v.x + (double)v.y * v.y) + ((double)v.z * v.z + (double)v.w * v.w);
   }
   acc = wave_sum(acc);
   bad = __any(bad);
@@ -35,6 +37,31 @@ __global__ __launch_bounds__(256) void grad_sumsq_kernel(const float4* __restric
     partial_sq[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
     partial_nf[blockIdx.x] = redf[0] | redf[1] | redf[2] | redf[3];
   }
+}
+
+// Level 2: workgroup b adds partials [b * kSumsqFan, (b + 1) * kSumsqFan) in a fixed order.
+__global__ __launch_bounds__(256) void grad_sumsq_mid_kernel(const double* __restrict__ in_sq,
+                                                             const int* __restrict__ in_nf, size_t count,
+                                                             double* __restrict__ out_sq,
+                                                             int* __restrict__ out_nf) {
+  __shared__ double red[256];
+  __shared__ int redf[256];
+  constexpr int per = kSumsqFan / 256;
+  double acc = 0.0;
+  int bad = 0;
+#pragma unroll
+  for (int k = 0; k < per; ++k) {
+    const size_t i = (size_t)blockIdx.x * kSumsqFan + (size_t)threadIdx.x * per + k;
+    if (i < count) { acc += in_sq[i]; bad |= in_nf[i]; }
+  }
+  red[threadIdx.x] = acc;
+  redf[threadIdx.x] = bad;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) { red[threadIdx.x] += red[threadIdx.x + o]; redf[threadIdx.x] |= redf[threadIdx.x + o]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { out_sq[blockIdx.x] = red[0]; out_nf[blockIdx.x] = redf[0]; }
 }
 
 // one workgroup; partial sums are added in a fixed order
@@ -161,8 +188,8 @@ __global__ __launch_bounds__(256) void adamw_step_kernel(float4* __restrict__ th
                                                          size_t n4, OptHyper hp, const OptDevState* __restrict__ st) {
   if (!st->do_step) return;
   const float coef = st->step_coef, bc1 = st->bc1, bc2 = st->bc2;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) {
     float4 th = theta[i], mm = m[i], vv = v[i], gg = g[i];
     if (JOURNAL) { j_theta[i] = th; j_m[i] = mm; j_v[i] = vv; }
     if (coef != 1.0f) { gg.x *= coef; gg.y *= coef; gg.z *= coef; gg.w *= coef; }
@@ -219,20 +246,30 @@ __global__ __launch_bounds__(256) void adamw_rollback_kernel(float4* __restrict_
   }
 }
 
-inline int opt_grid(size_t n4) {
-  size_t b = (n4 + 255) / 256;
-  return (int)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
-}
+// One 16-byte element per thread and as many 256-thread workgroups as that takes: the workgroups
+// start in index order, so the chip sweeps every array as one moving front, which the HBM likes
+// better than a grid-stride loop (measured: read-modify-write 5.9 TB/s against 4.5-4.9).
+inline unsigned opt_grid(size_t n4) { return (unsigned)((n4 + 255) / 256); }
 
 }  // namespace
 
+size_t grad_sumsq_partials(size_t n) {
+  const size_t p1 = (n / 4 + 255) / 256, p2 = (p1 + kSumsqFan - 1) / kSumsqFan;
+  return p1 + p2;
+}
+
 hipError_t launch_grad_sumsq(const float* g, size_t n, double* partial_sq, int* partial_nf, OptDevState* st,
                              hipStream_t s) {
-  if (n % 4 != 0) return hipErrorInvalidValue;
-  grad_sumsq_kernel<<<kSumsqBlocks, 256, 0, s>>>((const float4*)g, n / 4, partial_sq, partial_nf);
+  if (n % 4 != 0 || n == 0) return hipErrorInvalidValue;
+  const size_t n4 = n / 4;
+  const size_t p1 = (n4 + 255) / 256, p2 = (p1 + kSumsqFan - 1) / kSumsqFan;
+  if (p1 > ((size_t)1 << 31) - 1) return hipErrorInvalidValue;
+  grad_sumsq_kernel<<<(unsigned)p1, 256, 0, s>>>((const float4*)g, n4, partial_sq, partial_nf);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  grad_sumsq_final_kernel<<<1, 256, 0, s>>>(partial_sq, partial_nf, kSumsqBlocks, st);
+  grad_sumsq_mid_kernel<<<(unsigned)p2, 256, 0, s>>>(partial_sq, partial_nf, p1, partial_sq + p1, partial_nf + p1);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  grad_sumsq_final_kernel<<<1, 256, 0, s>>>(partial_sq + p1, partial_nf + p1, (int)p2, st);
   return hipGetLastError();
 }
 hipError_t launch_decide_optimistic(OptDevState* st, OptHyper hp, double prev_sq, int prev_nf, int force,
@@ -259,7 +296,8 @@ hipError_t launch_adamw_step(float* theta, float* m, float* v, const float* g, f
                              hipStream_t s) {
   if (n % 4 != 0) return hipErrorInvalidValue;
   const size_t n4 = n / 4;
-  const int grid = opt_grid(n4);
+  if (n4 == 0 || n4 > ((size_t)1 << 39)) return hipErrorInvalidValue;
+  const unsigned grid = opt_grid(n4);
   const bool J = j_theta != nullptr, H = theta16 != nullptr;
 #define ZB_STEP(JJ, HH)                                                                                          \
   adamw_step_kernel<JJ, HH><<<grid, 256, 0, s>>>((float4*)theta, (float4*)m, (float4*)v, (const float4*)g,        \
@@ -277,7 +315,9 @@ hipError_t launch_adamw_rollback(float* theta, float* m, float* v, const float* 
                                  OptDevState* st, hipStream_t s) {
   if (n % 4 != 0) return hipErrorInvalidValue;
   const size_t n4 = n / 4;
-  const int grid = opt_grid(n4);
+  if (n4 == 0 || n4 > ((size_t)1 << 39)) return hipErrorInvalidValue;
+  // grid-stride here: the mismatch count costs one atomic per wavefront, and a rollback is the rare path
+  const unsigned grid = opt_grid(n4) < 8192u ? opt_grid(n4) : 8192u;
   const bool J = j_theta != nullptr, H = theta16 != nullptr;
 #define ZB_RB(JJ, HH)                                                                                             \
   adamw_rollback_kernel<JJ, HH><<<grid, 256, 0, s>>>((float4*)theta, (float4*)m, (float4*)v, (const float4*)g,     \

@@ -2,6 +2,8 @@
 // (with the gamma/beta gradients, which this build produces in the B pass), bias-gradient
 // column sums (W pass), fills and type conversions.  One wavefront = 64 lanes; reductions
 // use cross-lane shuffles, then LDS across the four waves of a 256-thread workgroup.
+#include <cstdint>
+
 #include "zb_common.h"
 
 namespace zb {
@@ -294,10 +296,46 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const unsigned shor
   }
 }
 
+// 64 x 64 tile with 16-byte global accesses on both sides (rows, cols multiples of 64, 16-byte aligned
+// pointers).  LDS row pitch 66 elements: the gather of 8 consecutive rows of one column by 8 x 8 lanes
+// (stride 8 rows = 8 banks) touches every bank once.
+__global__ __launch_bounds__(256) void transpose_bf16_wide_kernel(const unsigned short* __restrict__ src,
+                                                                  unsigned short* __restrict__ dst, int rows,
+                                                                  int cols) {
+  constexpr int P = 66;
+  __shared__ __align__(4) unsigned short tile[64 * P];
+  const size_t r0 = (size_t)blockIdx.y * 64, c0 = (size_t)blockIdx.x * 64;
+  const int hi = threadIdx.x >> 3, lo = threadIdx.x & 7;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int r = hi + 32 * j;
+    const uint4 v = *reinterpret_cast<const uint4*>(src + (r0 + r) * cols + c0 + lo * 8);
+    unsigned* t = reinterpret_cast<unsigned*>(tile + r * P + lo * 8);
+    t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int c = hi + 32 * j;
+    unsigned w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const unsigned a = tile[(lo * 8 + 2 * k) * P + c], b = tile[(lo * 8 + 2 * k + 1) * P + c];
+      w[k] = a | (b << 16);
+    }
+    *reinterpret_cast<uint4*>(dst + (c0 + c) * rows + r0 + lo * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 __global__ void fill_f32_kernel(float* p, size_t n, float v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) p[i] = v;
+}
+// one 16-byte store per thread, workgroups in index order: the array is written as one moving front
+__global__ __launch_bounds__(256) void fill_f32x4_kernel(float4* p, size_t n4, float v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) p[i] = make_float4(v, v, v, v);
 }
 template <typename T>
 __global__ void convert_from_f32_kernel(const float* __restrict__ s, T* __restrict__ d, size_t n) {
@@ -380,13 +418,18 @@ hipError_t launch_colsum_accum(const T* dy, float* db, float* scratch, int rows,
 hipError_t launch_transpose_bf16(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t s) {
   if (rows <= 0 || cols <= 0) return hipErrorInvalidValue;
   dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-  transpose_bf16_kernel<<<grid, 256, 0, s>>>((const unsigned short*)src, (unsigned short*)dst, rows, cols);
+  const bool wide = rows % 64 == 0 && cols % 64 == 0 &&
+                    ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) == 0;
+  if (wide) transpose_bf16_wide_kernel<<<grid, 256, 0, s>>>((const unsigned short*)src, (unsigned short*)dst, rows, cols);
+  else transpose_bf16_kernel<<<grid, 256, 0, s>>>((const unsigned short*)src, (unsigned short*)dst, rows, cols);
   return hipGetLastError();
 }
 
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
   if (n == 0) return hipSuccess;
-  fill_f32_kernel<<<grid_for(n), 256, 0, s>>>(p, n, v);
+  const size_t n4 = (reinterpret_cast<uintptr_t>(p) & 15) == 0 ? n / 4 : 0;
+  if (n4 > 0 && n4 <= ((size_t)1 << 39)) fill_f32x4_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, s>>>((float4*)p, n4, v);
+  if (n > 4 * n4) fill_f32_kernel<<<grid_for(n - 4 * n4), 256, 0, s>>>(p + 4 * n4, n - 4 * n4, v);
   return hipGetLastError();
 }
 template <typename T> hipError_t launch_convert_from_f32(const float* src, T* dst, size_t n, hipStream_t s) {

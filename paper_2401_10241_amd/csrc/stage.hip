@@ -253,8 +253,9 @@ size_t layout(zb_stage* st, void* arena) {
     st->gemm_ws_floats = (size_t)4 * T * h;
     st->gemm_ws = bp.take<float>(st->gemm_ws_floats * sizeof(float));
   }
-  st->partial_sq = bp.take<double>(kSumsqBlocks * sizeof(double));
-  st->partial_nf = bp.take<int>(kSumsqBlocks * sizeof(int));
+  const size_t nsq = grad_sumsq_partials(st->flat_count);
+  st->partial_sq = bp.take<double>(nsq * sizeof(double));
+  st->partial_nf = bp.take<int>(nsq * sizeof(int));
   st->opt = bp.take<OptDevState>(sizeof(OptDevState));
   return align_up(bp.off);
 }

@@ -148,7 +148,11 @@ struct OptHyper {
   float lr, beta1, beta2, eps, weight_decay, clip;
 };
 
-constexpr int kSumsqBlocks = 1024;
+// Sum of squares and non-finite flag of n gradients (n % 4 == 0) in three levels, every sum in a fixed
+// order: per workgroup of 1024 elements, per kSumsqFan of those, then one workgroup.  partial_sq and
+// partial_nf need grad_sumsq_partials(n) entries each.
+constexpr int kSumsqFan = 1024;
+size_t grad_sumsq_partials(size_t n);
 hipError_t launch_grad_sumsq(const float* g, size_t n, double* partial_sq, int* partial_nf,
                              OptDevState* st, hipStream_t s);
 hipError_t launch_decide_optimistic(OptDevState* st, OptHyper hp, double prev_sq, int prev_nf, int force,
