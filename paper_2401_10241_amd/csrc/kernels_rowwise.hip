@@ -270,6 +270,59 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __res
     }
   }
 }
+// The same for up to four matrices of one row count in one launch (the four dY of a layer's W pass):
+// column blocks of the matrices are laid side by side, out[slice][total columns].
+template <typename T, int kV>
+__global__ __launch_bounds__(kThreads) void colsum_partial_multi_kernel(ColsumSegs sg, float* __restrict__ out,
+                                                                        int rows, int rows_per_slice) {
+  __shared__ float red[16][16 * kV + 1];
+  int seg = 0;
+#pragma unroll
+  for (int q = 1; q < 4; ++q) seg += (int)blockIdx.x >= sg.blk0[q] ? 1 : 0;
+  const int n = sg.n[seg];
+  const T* __restrict__ dy = (const T*)sg.dy[seg];
+  const int blk = blockIdx.x - sg.blk0[seg];
+  const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
+  const int col = (blk * 16 + cl) * kV;
+  const int r_begin = blockIdx.y * rows_per_slice;
+  const int r_end = min(rows, r_begin + rows_per_slice);
+  float acc[kV];
+#pragma unroll
+  for (int e = 0; e < kV; ++e) acc[e] = 0.f;
+  if (col < n) {
+    for (int r = r_begin + rg; r < r_end; r += 16) {
+      const T* p = dy + (size_t)r * n + col;
+#pragma unroll
+      for (int e = 0; e < kV; e += 4) {
+        float v[4];
+        Vec4<T>::load(p + e, v);
+        acc[e] += v[0]; acc[e + 1] += v[1]; acc[e + 2] += v[2]; acc[e + 3] += v[3];
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < kV; ++e) red[rg][cl * kV + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < 16 * kV) {
+    const int c = blk * 16 * kV + threadIdx.x;
+    if (c < n) {
+      float t = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t += red[r][threadIdx.x];
+      out[(size_t)blockIdx.y * sg.total + sg.col0[seg] + c] = t;
+    }
+  }
+}
+__global__ void colsum_final_multi_kernel(ColsumSegs sg, const float* __restrict__ part, int slices) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= sg.total) return;
+  int seg = 0;
+#pragma unroll
+  for (int q = 1; q < 4; ++q) seg += c >= sg.col0[q] ? 1 : 0;
+  float t = 0.f;
+  for (int k = 0; k < slices; ++k) t += part[(size_t)k * sg.total + c];
+  sg.db[seg][c - sg.col0[seg]] += t;
+}
 // stage 2: db[c] += slices added in order
 __global__ void colsum_final_kernel(const float* __restrict__ part, float* __restrict__ db, int slices, int n) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -415,6 +468,36 @@ hipError_t launch_colsum_accum(const T* dy, float* db, float* scratch, int rows,
   return hipGetLastError();
 }
 
+template <typename T>
+hipError_t launch_colsum_accum_multi(const void* const* dy, float* const* db, const int* n, int count, float* scratch,
+                                     int rows, hipStream_t s) {
+  constexpr int kV = 16 / sizeof(T);
+  constexpr int per_block = 16 * kV;
+  if (count < 1 || count > 4 || rows <= 0) return hipErrorInvalidValue;
+  ColsumSegs sg{};
+  int blocks = 0, cols = 0;
+  for (int q = 0; q < 4; ++q) {
+    const int nq = q < count ? n[q] : 0;
+    if (q < count && (nq <= 0 || nq % kV != 0 || !dy[q] || !db[q])) return hipErrorInvalidValue;
+    sg.dy[q] = q < count ? dy[q] : dy[0];
+    sg.db[q] = q < count ? db[q] : db[0];
+    sg.n[q] = nq;
+    sg.blk0[q] = blocks;
+    sg.col0[q] = cols;
+    blocks += (nq + per_block - 1) / per_block;
+    cols += nq;
+  }
+  for (int q = count; q < 4; ++q) { sg.blk0[q] = 0x7fffffff; sg.col0[q] = 0x7fffffff; }  // never selected
+  sg.total = cols;
+  const int slices = rows >= 8 * 16 ? kColsumSlices : 1;
+  colsum_partial_multi_kernel<T, kV><<<dim3(blocks, slices), kThreads, 0, s>>>(sg, scratch, rows,
+                                                                              (rows + slices - 1) / slices);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  colsum_final_multi_kernel<<<(cols + 255) / 256, 256, 0, s>>>(sg, scratch, slices);
+  return hipGetLastError();
+}
+
 hipError_t launch_transpose_bf16(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t s) {
   if (rows <= 0 || cols <= 0) return hipErrorInvalidValue;
   dim3 grid((cols + 63) / 64, (rows + 63) / 64);
@@ -452,7 +535,9 @@ template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStr
                                               hipStream_t);                                                      \
   template hipError_t launch_layernorm_bwd<T>(const T*, const T*, const float*, const float*, const T*, T*,      \
                                               float*, float*, float*, int, int, hipStream_t);                    \
-  template hipError_t launch_colsum_accum<T>(const T*, float*, float*, int, int, hipStream_t);                           \
+  template hipError_t launch_colsum_accum<T>(const T*, float*, float*, int, int, hipStream_t);                   \
+  template hipError_t launch_colsum_accum_multi<T>(const void* const*, float* const*, const int*, int, float*,  \
+                                                   int, hipStream_t);                                           \
   template hipError_t launch_convert_from_f32<T>(const float*, T*, size_t, hipStream_t);                         \
   template hipError_t launch_convert_to_f32<T>(const T*, float*, size_t, hipStream_t);                           \
   template hipError_t launch_poke<T>(T*, size_t, float, hipStream_t);

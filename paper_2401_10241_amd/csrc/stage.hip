@@ -240,8 +240,8 @@ size_t layout(zb_stage* st, void* arena) {
   st->dvec = bp.take<float>((size_t)st->b * st->a * st->s * sizeof(float));
   {  // LayerNorm-backward partials; the bias-gradient column sums reuse it for their row slices
     size_t need = (size_t)kLnBwdSlices * 2 * h;
-    const size_t widest = f > 3 * h ? f : 3 * h;
-    if ((size_t)kColsumSlices * widest > need) need = (size_t)kColsumSlices * widest;
+    const size_t all_dy = (size_t)h + f + h + 3 * h;  // the four dY of a layer side by side
+    if ((size_t)kColsumSlices * all_dy > need) need = (size_t)kColsumSlices * all_dy;
     st->ln_partials = bp.take<float>(need * sizeof(float));
   }
   size_t stg = h * f;
@@ -500,8 +500,14 @@ template <typename T> struct Exec {
         g.a_sm = 1; g.a_sk = pr.kin; g.b_sk = pr.nout; g.b_sn = 1;
         g.epilogue = EPI_ACCUM_F32; g.outf = st->G(l, pr.wi);
         ZB_HIP(st, gemm(st, KC_GEMM_WGRAD, g));
-        ProfScope ps(st, KC_COLSUM, 0, E * T_ * pr.nout);
-        ZB_HIP(st, launch_colsum_accum<T>(pr.dy, st->G(l, pr.bi), st->ln_partials, T_, pr.nout, s));
+      }
+      {  // the four bias gradients: column sums of the same dY's
+        const void* dys[4];
+        float* dbs[4];
+        int ns[4];
+        for (int q = 0; q < 4; ++q) { dys[q] = pairs[q].dy; dbs[q] = st->G(l, pairs[q].bi); ns[q] = pairs[q].nout; }
+        ProfScope ps(st, KC_COLSUM, 0, E * T_ * (double)(ns[0] + ns[1] + ns[2] + ns[3]));
+        ZB_HIP(st, launch_colsum_accum_multi<T>(dys, dbs, ns, 4, st->ln_partials, T_, s));
       }
     }
     return ZB_OK;
@@ -554,11 +560,20 @@ template <typename T> struct Exec {
                        8.0 * g.M * g.N + E * (double)g.K * ((double)g.M + g.N) * n);
           ZB_HIP(st, launch_gemm<T>(g, s));
         }
-        for (int i = 0; i < n; ++i) {
-          ProfScope ps(st, KC_COLSUM, 0, E * T_ * ln.nout);
-          ZB_HIP(st, launch_colsum_accum<T>((const T*)g.group_b[i], st->G(l, ln.bi), st->ln_partials, T_, ln.nout,
-                                            s));
+      }
+      for (int i = 0; i < n; ++i) {  // bias gradients, microbatch by microbatch in the group's order
+        const int mb = mbs[i];
+        const char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
+        const void* dys[4];
+        float* dbs[4];
+        int ns[4];
+        for (int q = 0; q < 4; ++q) {
+          dys[q] = lins[q].top_dy ? (const char*)(st->in_dy + st->act_bytes * (size_t)mb) : bw + lins[q].bw_off;
+          dbs[q] = st->G(l, lins[q].bi);
+          ns[q] = lins[q].nout;
         }
+        ProfScope ps(st, KC_COLSUM, 0, E * T_ * (double)(ns[0] + ns[1] + ns[2] + ns[3]));
+        ZB_HIP(st, launch_colsum_accum_multi<T>(dys, dbs, ns, 4, st->ln_partials, T_, s));
       }
     }
     return ZB_OK;

@@ -119,6 +119,19 @@ constexpr int kLnBwdSlices = 16;
 constexpr int kColsumSlices = 8;
 template <typename T>
 hipError_t launch_colsum_accum(const T* dy, float* db, float* scratch, int rows, int n, hipStream_t s);
+// the same for `count` <= 4 matrices dy[q] of [rows, n[q]] in one launch pair; every db[q][c] gets exactly the
+// sum the single call gives it; scratch holds kColsumSlices * (n[0] + ... + n[count-1]) floats
+struct ColsumSegs {
+  const void* dy[4];
+  float* db[4];
+  int n[4];
+  int blk0[4];  // first column block of each matrix in the launch
+  int col0[4];  // first column of each matrix in the scratch rows
+  int total;    // n[0] + ... + n[count-1]
+};
+template <typename T>
+hipError_t launch_colsum_accum_multi(const void* const* dy, float* const* db, const int* n, int count,
+                                     float* scratch, int rows, hipStream_t s);
 
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_transpose_bf16(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t s);
