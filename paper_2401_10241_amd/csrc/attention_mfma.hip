@@ -559,12 +559,12 @@ template <typename T> hipError_t launch_attention_bwd_mfma(const AttnArgs& a, hi
 template <> hipError_t launch_attention_fwd_mfma<bf16_t>(const AttnArgs& a, hipStream_t s, bool* taken) {
   *taken = mfma_shape(a);
   if (!*taken) return hipSuccess;
-  return a.d == 64 ? run_fwd<64>(a, s) : a.d == 96 ? run_fwd<96>(a, s) : launch_attention_fwd_d128(a, s);
+  return a.d == 64 ? run_fwd<64>(a, s) : launch_attention_fwd_d128(a, s);
 }
 template <> hipError_t launch_attention_bwd_mfma<bf16_t>(const AttnArgs& a, hipStream_t s, bool* taken) {
   *taken = mfma_shape(a);
   if (!*taken) return hipSuccess;
-  return a.d == 64 ? run_bwd<64>(a, s) : a.d == 96 ? run_bwd<96>(a, s) : launch_attention_bwd_d128(a, s);
+  return a.d == 64 ? run_bwd<64>(a, s) : launch_attention_bwd_d128(a, s);
 }
 template hipError_t launch_attention_fwd_mfma<float>(const AttnArgs&, hipStream_t, bool*);
 template hipError_t launch_attention_bwd_mfma<float>(const AttnArgs&, hipStream_t, bool*);

@@ -1,4 +1,4 @@
-// Causal attention forward for head size 128 on the gfx950 matrix cores, tuned variant of the general
+// Causal attention for head sizes 128 and 96 on the gfx950 matrix cores, tuned variant of the general
 // kernel in attention_mfma.hip (same mathematics, same transposed-product formulation, same results
 // layout): K and V tiles go global memory -> LDS directly (global_load_lds_dwordx4, no staging
 // registers), two workgroups share a compute unit so that one's softmax and loads hide behind the other's
@@ -15,10 +15,10 @@ namespace zb {
 
 namespace {
 
-constexpr int D = 128;
+constexpr int RP = 128;  // LDS row pitch in elements (256 B) for every head size
 constexpr int QB = 128;  // queries per workgroup (4 waves x 32)
 constexpr int KB = 64;   // keys per tile
-constexpr int TILE = KB * D;
+constexpr int TILE = KB * RP;
 constexpr float kLn2 = 0.6931471805599453f;
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -28,13 +28,17 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
-// global [64][128] tile (row stride ld) -> LDS stage s
+// global [64][D] tile (row stride ld) -> LDS stage s.  A head size below 128 leaves the chunk positions
+// of columns D..127 unused: their lanes fetch a chunk of the same row again (never read from LDS).
+template <int D>
 __device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ base, long ld, bf16_t* s, int wave, int lane) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int blk = j * 4 + wave;
     const int P = blk * 64 + lane;
-    const int row = P >> 4, c = (P & 15) ^ swz(row);
+    const int row = P >> 4;
+    int c = (P & 15) ^ swz(row);
+    if (D < 128 && c >= D / 8) c -= D / 8;
     __builtin_amdgcn_global_load_lds((gptr_t)(base + (long)row * ld + c * 8), (lptr_t)(s + blk * 512), 16, 0, 0);
   }
 }
@@ -42,7 +46,7 @@ __device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ base, long l
 __device__ __forceinline__ bf16x8 frag_rowk(const bf16_t* __restrict__ s, int rb, int kk, int lane) {
   const int row = rb + (lane & 31);
   const int chunk = kk * 2 + (lane >> 5);
-  return *reinterpret_cast<const bf16x8*>(s + row * D + ((chunk ^ swz(row)) << 3));
+  return *reinterpret_cast<const bf16x8*>(s + row * RP + ((chunk ^ swz(row)) << 3));
 }
 // operand fragment: rows = columns eb..eb+31 of the tile, k = tile rows in accumulator order
 // (slots 0-3 = rows kl0 + 4*(lane>>5) + 0..3, slots 4-7 = the same + 8)
@@ -51,8 +55,8 @@ __device__ __forceinline__ bf16x8 frag_tr(const bf16_t* __restrict__ s, int eb, 
   const int e = eb + ((blk & 1) << 4) + ((a & 3) << 2);
   const int kl = kl0 + ((blk >> 1) << 2) + (a >> 2);
   typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-  const bf16_t* p0 = s + kl * D + ((((e >> 3) ^ swz(kl)) << 3) | (e & 7));
-  const bf16_t* p1 = s + (kl + 8) * D + ((((e >> 3) ^ swz(kl + 8)) << 3) | (e & 7));
+  const bf16_t* p0 = s + kl * RP + ((((e >> 3) ^ swz(kl)) << 3) | (e & 7));
+  const bf16_t* p1 = s + (kl + 8) * RP + ((((e >> 3) ^ swz(kl + 8)) << 3) | (e & 7));
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p0);
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p1);
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -94,6 +98,7 @@ __device__ __forceinline__ void map_block(int nrb, int a, int b, bool first_heav
   *bi = hl / a;
 }
 
+template <int D>
 __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                              float* __restrict__ lse, int s, int a, float sl2) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
@@ -111,8 +116,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
   const int nkb = 2 * qb + 2;
   const bf16_t* kbase = qkv + tok0 * ld + h + head * D;
   const bf16_t* vbase = kbase + h;
-  dma_tile(kbase, ld, sK, wave, lane);
-  dma_tile(vbase, ld, sV, wave, lane);
+  dma_tile<D>(kbase, ld, sK, wave, lane);
+  dma_tile<D>(vbase, ld, sV, wave, lane);
 
   bf16x8 qf[D / 16];
   {
@@ -134,8 +139,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
     __builtin_amdgcn_s_waitcnt(kWaitVm0);  // this wave's part of tile jb has landed
     __builtin_amdgcn_s_barrier();          // everyone's has; everyone is done with the other stage
     if (jb + 1 < nkb) {
-      dma_tile(kbase + (long)(jb + 1) * KB * ld, ld, sK + ((jb + 1) & 1) * TILE, wave, lane);
-      dma_tile(vbase + (long)(jb + 1) * KB * ld, ld, sV + ((jb + 1) & 1) * TILE, wave, lane);
+      dma_tile<D>(kbase + (long)(jb + 1) * KB * ld, ld, sK + ((jb + 1) & 1) * TILE, wave, lane);
+      dma_tile<D>(vbase + (long)(jb + 1) * KB * ld, ld, sV + ((jb + 1) & 1) * TILE, wave, lane);
     }
     const bf16_t* kc = sK + (jb & 1) * TILE;
     const bf16_t* vc = sV + (jb & 1) * TILE;
@@ -214,12 +219,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
 // ------------------------------------------------------------------------------------------------
 // backward, D_i = dO_i . O_i  (one wavefront per (row, head))
 // ------------------------------------------------------------------------------------------------
+template <int D>
 __global__ __launch_bounds__(64) void attn_bwd128_prep_kernel(const bf16_t* __restrict__ o,
                                                               const bf16_t* __restrict__ dout,
                                                               float* __restrict__ dvec, int s, int a) {
   const int i = blockIdx.x, head = blockIdx.y, bi = blockIdx.z;
   const long off = ((long)bi * s + i) * a * D + head * D + threadIdx.x * 2;
-  float acc = (float)o[off] * (float)dout[off] + (float)o[off + 1] * (float)dout[off + 1];
+  float acc = 0.f;
+  if ((int)threadIdx.x * 2 < D) acc = (float)o[off] * (float)dout[off] + (float)o[off + 1] * (float)dout[off + 1];
   acc = wave_sum(acc);
   if (threadIdx.x == 0) dvec[((long)bi * a + head) * s + i] = acc;
 }
@@ -227,6 +234,7 @@ __global__ __launch_bounds__(64) void attn_bwd128_prep_kernel(const bf16_t* __re
 // ------------------------------------------------------------------------------------------------
 // backward, dQ: workgroup = 128 queries, loop over key tiles up to the diagonal (same pipeline as forward)
 // ------------------------------------------------------------------------------------------------
+template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bwd128_dq_kernel(const bf16_t* __restrict__ qkv,
                                                              const bf16_t* __restrict__ dout,
                                                              const float* __restrict__ lse,
@@ -249,8 +257,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd128_dq_kernel(const bf16_t* __
   const bf16_t* kbase = qkv + tok0 * ld + h + head * D;
   const bf16_t* vbase = kbase + h;
   auto issue = [&](int t) {  // 8 DMA instructions per wave
-    dma_tile(kbase + (long)t * KB * ld, ld, sK + (t & 1) * TILE, wave, lane);
-    dma_tile(vbase + (long)t * KB * ld, ld, sV + (t & 1) * TILE, wave, lane);
+    dma_tile<D>(kbase + (long)t * KB * ld, ld, sK + (t & 1) * TILE, wave, lane);
+    dma_tile<D>(vbase + (long)t * KB * ld, ld, sV + (t & 1) * TILE, wave, lane);
   };
   issue(0);
 
@@ -339,6 +347,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd128_dq_kernel(const bf16_t* __
 // statistics (waves 0/1 fetch lse / D, waves 2/3 fetch the same again into a spare area so that every
 // wave has the same number of loads in flight).
 // ------------------------------------------------------------------------------------------------
+template <int D>
 __global__ __launch_bounds__(256) void attn_bwd128_dkv_kernel(const bf16_t* __restrict__ qkv,
                                                               const bf16_t* __restrict__ dout,
                                                               const float* __restrict__ lse,
@@ -364,8 +373,8 @@ __global__ __launch_bounds__(256) void attn_bwd128_dkv_kernel(const bf16_t* __re
   const float* stat = ((wave & 1) ? dvec : lse) + ((long)bi * a + head) * s;
   auto issue = [&](int ib) {  // 9 DMA instructions per wave
     const int st = (ib - ib0) % 3;
-    dma_tile(qbase + (long)ib * KB * ld, ld, sQ + st * TILE, wave, lane);
-    dma_tile(obase + (long)ib * KB * h, h, sO + st * TILE, wave, lane);
+    dma_tile<D>(qbase + (long)ib * KB * ld, ld, sQ + st * TILE, wave, lane);
+    dma_tile<D>(obase + (long)ib * KB * h, h, sO + st * TILE, wave, lane);
     __builtin_amdgcn_global_load_lds((gptr_t)(stat + ib * KB + lane), (lptr_t)(sS + (st * 4 + wave) * 64), 4, 0, 0);
   };
   issue(ib0);
@@ -463,49 +472,61 @@ __global__ __launch_bounds__(256) void attn_bwd128_dkv_kernel(const bf16_t* __re
     }
 }
 
-}  // namespace
-
-hipError_t launch_attention_fwd_d128(const AttnArgs& a, hipStream_t s) {
+template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
   constexpr size_t smem = (size_t)4 * TILE * sizeof(bf16_t);
   if (!done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd128_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd128_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     done = true;
   }
   dim3 grid((a.s / QB) * a.a * a.b);
-  attn_fwd128_kernel<<<grid, 256, smem, s>>>((const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.s, a.a,
-                                             1.4426950408889634f / sqrtf((float)D));
+  attn_fwd128_kernel<D><<<grid, 256, smem, s>>>((const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.s, a.a,
+                                                1.4426950408889634f / sqrtf((float)D));
   return hipGetLastError();
 }
 
-hipError_t launch_attention_bwd_d128(const AttnArgs& a, hipStream_t s) {
+template <int D> hipError_t run_bwd_dma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
   constexpr size_t smem_q = (size_t)4 * TILE * sizeof(bf16_t);
   constexpr size_t smem_kv = (size_t)6 * TILE * sizeof(bf16_t) + 3 * 4 * 64 * sizeof(float);
   if (!done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dq_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dq_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_q);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dkv_kernel),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dkv_kernel<D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_kv);
     if (e != hipSuccess) return e;
     done = true;
   }
   const float scale = 1.0f / sqrtf((float)D);
   dim3 grid1(a.s, a.a, a.b);
-  attn_bwd128_prep_kernel<<<grid1, 64, 0, s>>>((const bf16_t*)a.o, (const bf16_t*)a.dout, a.dvec, a.s, a.a);
+  attn_bwd128_prep_kernel<D><<<grid1, 64, 0, s>>>((const bf16_t*)a.o, (const bf16_t*)a.dout, a.dvec, a.s, a.a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 grid((a.s / QB) * a.a * a.b);
-  attn_bwd128_dq_kernel<<<grid, 256, smem_q, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
-                                                  (bf16_t*)a.dqkv, a.s, a.a, scale);
+  attn_bwd128_dq_kernel<D><<<grid, 256, smem_q, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
+                                                     (bf16_t*)a.dqkv, a.s, a.a, scale);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  attn_bwd128_dkv_kernel<<<grid, 256, smem_kv, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
-                                                    (bf16_t*)a.dqkv, a.s, a.a, scale);
+  attn_bwd128_dkv_kernel<D><<<grid, 256, smem_kv, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
+                                                       (bf16_t*)a.dqkv, a.s, a.a, scale);
   return hipGetLastError();
+}
+
+}  // namespace
+
+// head sizes 96 and 128 (a.s a multiple of 128 tokens, checked by the caller)
+hipError_t launch_attention_fwd_d128(const AttnArgs& a, hipStream_t s) {
+  if (a.d == 128) return run_fwd_dma<128>(a, s);
+  if (a.d == 96) return run_fwd_dma<96>(a, s);
+  return hipErrorInvalidValue;
+}
+hipError_t launch_attention_bwd_d128(const AttnArgs& a, hipStream_t s) {
+  if (a.d == 128) return run_bwd_dma<128>(a, s);
+  if (a.d == 96) return run_bwd_dma<96>(a, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace zb
