@@ -224,6 +224,13 @@ def main():
                                "gbs": None if idle else round(r["bytes"] / ms / 1e6, 1)}
             if idle:
                 kern[r["name"]]["note"] = "predicated off on the device in this iteration"
+            if r["flops"] and r["bytes"] and r["name"].startswith("gemm_"):
+                # the lower of the matrix peak and what the algorithmic bytes allow at the HBM peak (the wgrad
+                # GEMMs with their fp32 read-modify-write sit near that ridge)
+                ceil_tf = min(PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS,
+                              r["flops"] / r["bytes"] * PEAK_HBM_GBS / 1e3)
+                kern[r["name"]]["ceiling_tflops"] = round(ceil_tf, 1)
+                kern[r["name"]]["frac_of_ceiling"] = round(r["flops"] / ms / 1e9 / ceil_tf, 4)
         gemm = [r for r in stats if r["name"].startswith("gemm_")]
         g_ms = sum(r["total_ms"] for r in gemm)
         g_fl = sum(r["flops"] for r in gemm)
