@@ -23,9 +23,14 @@
 //     lane a points at 4 consecutive rows (a & 3) * 4 of k-line (a >> 2) and receives, as lane r, the 4 k
 //     values of row r.  32 lanes read 64 B from each of four k-lines; the swizzle puts those in
 //     different quarters of the banks.
-//   K-contiguous source: 64 k at a time (128-byte rows, so every fetched cache line is used whole), two
-//     stages of [BM][64] refilled every other step; chunk c of row r sits at position c ^ ((r >> 1) & 7):
-//     16 consecutive rows reading the same k cover all banks.
+//   K-contiguous source: 64 k at a time (128-byte rows, so every fetched cache line is used whole), two or
+//     three stages of [BM][64] refilled every other step; chunk c of row r sits at position
+//     c ^ ((r >> 1) & 7): 16 consecutive rows reading the same k cover all banks.
+//
+// Ring shape for the 256-row tile: 3 A stages (96 KB) + 4 B stages (64 KB) = the whole 160 KB.  Loads come
+// back in order, so an A tile (activations, L2 hits) waits behind the B tiles (weights, streamed from
+// HBM) issued before it; fetching A two tiles (four steps) ahead and B three steps ahead balances the two
+// (about 1 % faster than 2 + 5 stages, which has more bytes of B in flight but A only two steps ahead).
 //
 // MFMA 32x32x16 operand layout: lane l supplies row (l & 31) of its operand and the 8 consecutive k
 // starting at 8 * (l >> 5); it receives column (l & 31) and rows 8*(v/4) + 4*(l >> 5) + v%4 of the
@@ -52,29 +57,45 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding)
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
-// global -> LDS, [32 k][R] tile of a row-contiguous operand (element (k, r) at p[k*ld + r])
+// Direct-to-LDS loads.  Every DMA instruction of a wave writes one 1 KB run of the tile (run index
+// blk = j * 8 + wave); which 16-byte global chunk a lane fetches implements the LDS swizzle.  The address
+// splits into a part that is the same for the whole wave (tile origin, k offset, run) and a per-lane byte
+// offset that never changes during the kernel, so the wave-uniform part is scalar arithmetic and the
+// lane offset one register per operand (`wave` must be a scalar: readfirstlane'd by the caller).
+//
+// [32 k][R] tile of a row-contiguous operand (element (k, r) at p[k*ld + r]): run blk holds k-lines
+// blk*LPB .. +LPB-1, LPB = 1024 B / (2R B).
+template <int R> __device__ __forceinline__ unsigned dma_tr_lane_off(long ld, int wave, int lane) {
+  constexpr int CPL = R / 8, LPB = 64 / CPL;  // chunks per k-line, k-lines per run
+  const int kl = lane / CPL;
+  const int k3 = (wave * LPB + kl) & 3;  // (k & 3): the runs of one wave are 8*LPB (a multiple of 4) lines apart
+  const int c = (lane % CPL) ^ (k3 << 2);
+  return (unsigned)((kl * ld + c * 8) * (long)sizeof(bf16_t));
+}
+// p0 = the tile's first element (k0, r0)
 template <int R>
-__device__ __forceinline__ void dma_tr(const bf16_t* __restrict__ p, long ld, int r0, int k0, bf16_t* s, int wave,
-                                       int lane) {
-  constexpr int CPL = R / 8;  // 16-byte chunks per k-line
+__device__ __forceinline__ void dma_tr(const bf16_t* __restrict__ p0, long ld, unsigned lane_off, bf16_t* s, int wave) {
+  constexpr int LPB = 64 / (R / 8);
 #pragma unroll
   for (int j = 0; j < R / 128; ++j) {
-    const int blk = j * 8 + wave;   // which 1 KB run of the tile
-    const int P = blk * 64 + lane;  // chunk position in LDS
-    const int k = P / CPL, c = (P % CPL) ^ ((k & 3) << 2);
-    __builtin_amdgcn_global_load_lds((gptr_t)(p + (long)(k0 + k) * ld + r0 + c * 8), (lptr_t)(s + blk * 512), 16, 0, 0);
+    const int blk = j * 8 + wave;
+    const char* base = reinterpret_cast<const char*>(p0 + (long)(blk * LPB) * ld);
+    __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)(s + blk * 512), 16, 0, 0);
   }
 }
-// global -> LDS, [R][64 k] tile of a K-contiguous operand (element (r, k) at p[r*ld + k])
+// [R][64 k] tile of a K-contiguous operand (element (r, k) at p[r*ld + k]): run blk holds rows blk*8 .. +7.
+__device__ __forceinline__ unsigned dma_rows_lane_off(long ld, int wave, int lane) {
+  const int rl = lane >> 3;
+  const int c = (lane & 7) ^ ((((wave & 1) << 2) | (lane >> 4)) & 7);  // ((r >> 1) & 7), r = blk*8 + rl
+  return (unsigned)((rl * ld + c * 8) * (long)sizeof(bf16_t));
+}
 template <int R>
-__device__ __forceinline__ void dma_rows(const bf16_t* __restrict__ p, long ld, int r0, int k0, bf16_t* s, int wave,
-                                         int lane) {
+__device__ __forceinline__ void dma_rows(const bf16_t* __restrict__ p0, long ld, unsigned lane_off, bf16_t* s, int wave) {
 #pragma unroll
   for (int j = 0; j < R / 64; ++j) {
     const int blk = j * 8 + wave;
-    const int P = blk * 64 + lane;
-    const int r = P >> 3, c = (P & 7) ^ ((r >> 1) & 7);
-    __builtin_amdgcn_global_load_lds((gptr_t)(p + (long)(r0 + r) * ld + k0 + c * 8), (lptr_t)(s + blk * 512), 16, 0, 0);
+    const char* base = reinterpret_cast<const char*>(p0 + (long)(blk * 8) * ld);
+    __builtin_amdgcn_global_load_lds((gptr_t)(base + lane_off), (lptr_t)(s + blk * 512), 16, 0, 0);
   }
 }
 
@@ -105,27 +126,33 @@ constexpr int even_steps_in_window(int BS, int parity) {
   return n;
 }
 
-template <int BM, int BS, bool ATR> struct Cfg {
+// AS = LDS stages of a K-contiguous A (64 k each, refilled on even steps AS-1 tiles ahead); a row-contiguous A
+// travels with B in the BS-stage ring.
+template <int BM, int BS, bool ATR, int AS = 2> struct Cfg {
   static constexpr int A_ELEMS = ATR ? KS * BM : BM * 64;      // per A stage
-  static constexpr int A_STAGES = ATR ? BS : 2;
+  static constexpr int A_STAGES = ATR ? BS : AS;
   static constexpr int B_ELEMS = KS * BN;
   static constexpr int LA = ATR ? BM / 128 : BM / 64;           // DMA instructions per wave per A refill
   static constexpr size_t SMEM = ((size_t)A_STAGES * A_ELEMS + (size_t)BS * B_ELEMS) * sizeof(bf16_t);
   // younger loads that may still be in flight when step `it` starts computing
   static constexpr int allowed(int parity) {
     if (ATR) return (BS - 2) * (LA + LB);
+    // after B tile `it`: the refills of steps it-BS+2 .. it-1
     const int wrt_b = (BS - 2) * LB + LA * even_steps_in_window(BS, parity);
     if (parity) return wrt_b;               // the A tile of this pair was checked on the even step
-    return wrt_b < 2 * LB ? wrt_b : 2 * LB;  // after A(it/2): B of step it-2 and of step it-1
+    // after A tile it/2 (issued on step it-2(AS-1), before that step's B): the B tiles of steps
+    // it-2(AS-1) .. it-1 and the A tiles of the AS-2 even steps between
+    const int wrt_a = 2 * (AS - 1) * LB + (AS - 2) * LA;
+    return wrt_b < wrt_a ? wrt_b : wrt_a;
   }
 };
 
-template <int BM, int BS, int MODE>
+template <int BM, int BS, int MODE, int AS>
 __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ B, int M, int N, int K,
                                                             long lda, long ldb, EpiParams epi, int ksplit) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  typedef Cfg<BM, BS, false> C;
+  typedef Cfg<BM, BS, false, AS> C;
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
   bf16_t* sB = sA + C::A_STAGES * C::A_ELEMS;
   constexpr int WM = BM / 2;
@@ -161,8 +188,11 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   const int m0 = (band * GROUP_M + in_band % band_rows) * BM;
   const int n0 = (in_band / band_rows) * BN;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
+  const unsigned a_off = dma_rows_lane_off(lda, wave, lane), b_off = dma_tr_lane_off<BN>(ldb, wave, lane);
+  const bf16_t* a_tile = A + (long)m0 * lda;  // + k
+  const bf16_t* b_tile = B + n0;              // + k * ldb
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -178,11 +208,12 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   // loads is the same from the first step on)
   auto issue = [&](int it) {
     if ((it & 1) == 0) {
-      const int j = (it >> 1) + 1;  // A tile j covers steps 2j, 2j+1 (j = -1 during the fill: nothing)
-      if (j >= 0 && 2 * j < nk) dma_rows<BM>(A, lda, m0, j * 64, sA + (j & 1) * C::A_ELEMS, wave, lane);
+      const int j = (it >> 1) + AS - 1;  // A tile j covers steps 2j, 2j+1 (negative early in the fill: nothing)
+      if (j >= 0 && 2 * j < nk) dma_rows<BM>(a_tile + j * 64, lda, a_off, sA + (j % AS) * C::A_ELEMS, wave);
     }
     const int nt = it + BS - 1;
-    if (nt < nk) dma_tr<BN>(B, ldb, n0, nt * KS, sB + (nt % BS) * C::B_ELEMS, wave, lane);
+    if (nt >= 0 && nt < nk)
+      dma_tr<BN>(b_tile + (long)(nt * KS) * ldb, ldb, b_off, sB + (nt % BS) * C::B_ELEMS, wave);
   };
   // With one workgroup per CU (BS > 3) the MFMAs of the second half of every tile are issued after the
   // NEXT step's barrier: a wave then reaches the barrier with matrix work still queued, and the matrix
@@ -192,7 +223,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   bf16x8 af1[MT], bf1[NT];  // fragments of the current tile's second half, kept across the barrier
   auto load_frags = [&](int it, int parity, int kk, bf16x8 (&af)[MT], bf16x8 (&bfr)[NT]) {
     const bf16_t* b_s = sB + (it % BS) * C::B_ELEMS;
-    const bf16_t* a_s = sA + ((it >> 1) & 1) * C::A_ELEMS;
+    const bf16_t* a_s = sA + ((it >> 1) % AS) * C::A_ELEMS;
 #pragma unroll
     for (int i = 0; i < MT; ++i) af[i] = frag_rows(a_s, wm + i * 32, parity * 2 + kk, lane);
 #pragma unroll
@@ -208,7 +239,8 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
   auto step = [&](int it, auto parity_tag) {
     constexpr int parity = decltype(parity_tag)::value;
     // near the end fewer loads were issued than the constant assumes: wait for everything
-    if (it + BS - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::allowed(parity)));
+    constexpr int AHEAD = (BS - 2) > (2 * AS - 3) ? (BS - 2) : (2 * AS - 3);  // last step whose refills all exist
+    if (it + AHEAD < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::allowed(parity)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
     // The refill of the stage that step it-1 used may be issued any time after the barrier; with the deep
@@ -230,8 +262,10 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
     }
   };
 
+  // pipeline fill: the same sequence of refills as in the loop, from the first step that issues anything
+  constexpr int FILL0 = (1 - BS) < -2 * (AS - 1) ? (1 - BS) : -2 * (AS - 1);
 #pragma unroll
-  for (int it = 1 - BS; it < 0; ++it) issue(it);
+  for (int it = FILL0; it < 0; ++it) issue(it);
   for (int it = 0; it < nk; it += 2) {
     step(it, std::integral_constant<int, 0>());
     step(it + 1, std::integral_constant<int, 1>());
@@ -248,10 +282,10 @@ __global__ __launch_bounds__(NTHREADS, (BM == 128 && BS == 3) ? 4 : 2) void gemm
 }
 
 // ldo: row stride of the outputs when the GEMM covers a column range of a wider matrix (0: g.N)
-template <int BM, int BS, int MODE>
+template <int BM, int BS, int MODE, int AS = 2>
 hipError_t run_cfg(const GemmArgs& g, long lda, long ldb, hipStream_t s, int ksplit = 1, int ldo = 0) {
-  auto kern = gemm_mfma_kernel<BM, BS, MODE>;
-  constexpr size_t smem = Cfg<BM, BS, false>::SMEM;
+  auto kern = gemm_mfma_kernel<BM, BS, MODE, AS>;
+  constexpr size_t smem = Cfg<BM, BS, false, AS>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool attr_set = false;  // one device per process in this library
   if (!attr_set) {
@@ -343,9 +377,10 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
   const int m0 = (band * GROUP_M + in_band % band_rows) * BM;
   const int n0 = (in_band / band_rows) * BN;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
   const int lrow = lane & 31, lhi = (lane >> 5) * 4;
+  const unsigned a_off = dma_tr_lane_off<BM>(lda, wave, lane), b_off = dma_tr_lane_off<BN>(ldb, wave, lane);
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -364,8 +399,8 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
   auto issue = [&](int it) {
     const int nt = it + BS - 1;
     if (nt < nk) {
-      dma_tr<BM>(gp.a[g_next], lda, m0, k_next, sA + (nt % BS) * C::A_ELEMS, wave, lane);
-      dma_tr<BN>(gp.b[g_next], ldb, n0, k_next, sB + (nt % BS) * C::B_ELEMS, wave, lane);
+      dma_tr<BM>(gp.a[g_next] + (long)k_next * lda + m0, lda, a_off, sA + (nt % BS) * C::A_ELEMS, wave);
+      dma_tr<BN>(gp.b[g_next] + (long)k_next * ldb + n0, ldb, b_off, sB + (nt % BS) * C::B_ELEMS, wave);
       k_next += KS;
       if (k_next == Kc) { k_next = 0; ++g_next; }
     }
@@ -441,7 +476,7 @@ bool try_split_k(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipError_
   GemmArgs p = g;
   p.epilogue = EPI_PARTIAL;
   p.outf = g.workspace;
-  *err = run_cfg<256, 5, EPI_PARTIAL>(p, lda, ldb, s, slices);
+  *err = run_cfg<256, 4, EPI_PARTIAL, 3>(p, lda, ldb, s, slices);
   if (*err != hipSuccess) return true;
   const size_t threads = plane / 4;
   gemm_splitk_fixup_kernel<MODE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(g.workspace, slices, plane, g.N,
@@ -468,7 +503,7 @@ bool try_tail_split(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipErr
   if ((size_t)slices * plane > g.workspace_floats) return false;
   GemmArgs a = g;
   a.N = n_main;
-  *err = run_cfg<256, 5, MODE>(a, lda, ldb, s, 1, g.N);
+  *err = run_cfg<256, 4, MODE, 3>(a, lda, ldb, s, 1, g.N);
   if (*err != hipSuccess) return true;
   GemmArgs t = g;  // the same GEMM on columns n_main .. N-1
   t.N = n_tail;
@@ -480,7 +515,7 @@ bool try_tail_split(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipErr
   GemmArgs p = t;
   p.epilogue = EPI_PARTIAL;
   p.outf = g.workspace;
-  *err = run_cfg<256, 5, EPI_PARTIAL>(p, lda, ldb, s, slices);
+  *err = run_cfg<256, 4, EPI_PARTIAL, 3>(p, lda, ldb, s, slices);
   if (*err != hipSuccess) return true;
   EpiParams epi = make_epi(t);
   epi.N = g.N;
@@ -504,7 +539,7 @@ hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool*
     const long t128 = g.M % 128 == 0 ? (long)(g.M / 128) * (g.N / BN) : 0;
     const double c256 = t256 ? (double)((t256 + 255) / 256) * 256.0 / 1.25 : 1e30;
     const double c128 = t128 ? (double)((t128 + 255) / 256) * 128.0 : 1e30;
-    if (t256 && c256 <= c128) return run_cfg<256, 5, MODE>(g, lda, ldb, s);
+    if (t256 && c256 <= c128) return run_cfg<256, 4, MODE, 3>(g, lda, ldb, s);
     if (t128) {
       // more tiles than CUs: a three-stage ring (<= 80 KB) lets two workgroups share a CU, so one's
       // epilogue and pipeline fill hide behind the other's MFMAs; otherwise one workgroup per CU with a
