@@ -360,6 +360,7 @@ SWEEP = [
     (384, 4, 1536, 192, 2, 1, "bf16"),    # head size 96
     (256, 2, 1024, 320, 1, 1, "fp32"),    # fp32 arithmetic everywhere
     (2048, 16, 8192, 512, 1, 1, "bf16"),  # split-K shapes with 512 tokens
+    (1536, 12, 6144, 256, 1, 1, "bf16"),  # wgrad on 128-row tiles, two workgroups per CU (288 tiles for FC1 / FC2)
 ]
 
 
