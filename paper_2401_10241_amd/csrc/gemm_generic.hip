@@ -7,6 +7,7 @@
 namespace zb {
 
 template <typename T> hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s, bool* taken);
+template <typename T> hipError_t launch_wgrad_multi_mfma(const WgradMultiArgs& w, hipStream_t s, bool* taken);
 
 namespace {
 
@@ -109,6 +110,30 @@ template <typename T> hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   return launch_gemm_generic<T>(g, s);
 }
 
+template <typename T> hipError_t launch_wgrad_multi(const WgradMultiArgs& w, hipStream_t s) {
+  if (w.nprob < 1 || w.nprob > kWgradMaxProblems || w.ngroup < 1 || w.ngroup > kGemmGroupMax ||
+      w.nprob * w.ngroup > kWgradMaxPairs || w.K <= 0)
+    return hipErrorInvalidValue;
+  bool taken = false;
+  hipError_t e = launch_wgrad_multi_mfma<T>(w, s, &taken);
+  if (taken) return e;
+  for (int q = 0; q < w.nprob; ++q) {  // problem by problem (fp32, or a shape the MFMA kernel does not take)
+    GemmArgs g{};
+    g.M = w.M[q]; g.N = w.N[q]; g.K = w.K;
+    g.a_sm = 1; g.a_sk = w.M[q]; g.b_sk = w.N[q]; g.b_sn = 1;
+    g.epilogue = EPI_ACCUM_F32; g.outf = w.outf[q];
+    g.A = w.a[q * w.ngroup]; g.B = w.b[q * w.ngroup];
+    if (w.ngroup >= 2) {
+      g.group = w.ngroup;
+      for (int i = 0; i < w.ngroup; ++i) { g.group_a[i] = w.a[q * w.ngroup + i]; g.group_b[i] = w.b[q * w.ngroup + i]; }
+    }
+    if ((e = launch_gemm<T>(g, s)) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template hipError_t launch_wgrad_multi<float>(const WgradMultiArgs&, hipStream_t);
+template hipError_t launch_wgrad_multi<bf16_t>(const WgradMultiArgs&, hipStream_t);
 template hipError_t launch_gemm<float>(const GemmArgs&, hipStream_t);
 template hipError_t launch_gemm<bf16_t>(const GemmArgs&, hipStream_t);
 template hipError_t launch_gemm_generic<float>(const GemmArgs&, hipStream_t);

@@ -349,16 +349,20 @@ __global__ __launch_bounds__(256) void gemm_splitk_fixup_kernel(const float* __r
 // and nothing is read back there.  An element's value is therefore the same chain of fp32 MFMA additions
 // whatever the tile shape, ring depth or grouping: `ngroup` pairs in one launch give exactly the bits of
 // `ngroup` launches of one pair.  The ring runs on across the pairs without draining.
-struct GroupPtrs {
-  const bf16_t* a[kGemmGroupMax];
-  const bf16_t* b[kGemmGroupMax];
+// One launch covers up to kWgradMaxProblems gradients (the weight matrices of one W pass: tiles of equal
+// duration, so the partly filled last round of workgroups is paid once per pass instead of once per
+// matrix) with `ngroup` operand pairs each.
+struct WgradTable {
+  int nprob, ngroup;
+  int tile0[kWgradMaxProblems + 1];  // first tile of each problem in the launch
+  int M[kWgradMaxProblems], N[kWgradMaxProblems];
+  float* outf[kWgradMaxProblems];
+  const bf16_t* a[kWgradMaxPairs];   // pair g of problem q at [q * ngroup + g]
+  const bf16_t* b[kWgradMaxPairs];
 };
 
 template <int BM, int BS, bool XB>
-__global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgrad_kernel(GroupPtrs gp, int ngroup,
-                                                                                       int M, int N, int Kc, long lda,
-                                                                                       long ldb,
-                                                                                       float* __restrict__ outf) {
+__global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgrad_kernel(WgradTable tb, int Kc) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   typedef Cfg<BM, BS, true> C;
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
@@ -366,10 +370,18 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
   constexpr int WM = BM / 2;
   constexpr int MT = WM / 32, NT = WN / 32;
 
-  const int tiles_m = M / BM, tiles_n = N / BN;
   const int nblk = gridDim.x;
   int pid = blockIdx.x;
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  int q = 0;  // which problem this tile belongs to
+#pragma unroll
+  for (int i = 1; i < kWgradMaxProblems; ++i) q += (i < tb.nprob && pid >= tb.tile0[i]) ? 1 : 0;
+  pid -= tb.tile0[q];
+  const int M = tb.M[q], N = tb.N[q], ngroup = tb.ngroup;
+  const long lda = M, ldb = N;
+  float* __restrict__ outf = tb.outf[q];
+  const int pair0 = q * ngroup;
+  const int tiles_m = M / BM, tiles_n = N / BN;
   constexpr int GROUP_M = 8;
   const int band = pid / (GROUP_M * tiles_n);
   const int band_rows = min(tiles_m - band * GROUP_M, GROUP_M);
@@ -399,8 +411,8 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
   auto issue = [&](int it) {
     const int nt = it + BS - 1;
     if (nt < nk) {
-      dma_tr<BM>(gp.a[g_next] + (long)k_next * lda + m0, lda, a_off, sA + (nt % BS) * C::A_ELEMS, wave);
-      dma_tr<BN>(gp.b[g_next] + (long)k_next * ldb + n0, ldb, b_off, sB + (nt % BS) * C::B_ELEMS, wave);
+      dma_tr<BM>(tb.a[pair0 + g_next] + (long)k_next * lda + m0, lda, a_off, sA + (nt % BS) * C::A_ELEMS, wave);
+      dma_tr<BN>(tb.b[pair0 + g_next] + (long)k_next * ldb + n0, ldb, b_off, sB + (nt % BS) * C::B_ELEMS, wave);
       k_next += KS;
       if (k_next == Kc) { k_next = 0; ++g_next; }
     }
@@ -554,15 +566,8 @@ hipError_t run_shape(const GemmArgs& g, long lda, long ldb, hipStream_t s, bool*
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-}  // namespace
-
-template <typename T> hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s, bool* taken) {
-  *taken = false;
-  return hipSuccess;
-}
-
 template <int BM, int BS, bool XB>
-hipError_t run_wgrad(const GroupPtrs& gp, const GemmArgs& g, int ngroup, long lda, long ldb, hipStream_t s) {
+hipError_t run_wgrad(WgradTable& tb, int K, hipStream_t s) {
   auto kern = gemm_wgrad_kernel<BM, BS, XB>;
   constexpr size_t smem = Cfg<BM, BS, true>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget");
@@ -573,35 +578,82 @@ hipError_t run_wgrad(const GroupPtrs& gp, const GemmArgs& g, int ngroup, long ld
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int grid = (g.M / BM) * (g.N / BN);
-  kern<<<grid, NTHREADS, smem, s>>>(gp, ngroup, g.M, g.N, g.K, lda, ldb, g.outf);
+  int tiles = 0;
+  for (int q = 0; q < tb.nprob; ++q) {
+    tb.tile0[q] = tiles;
+    tiles += (tb.M[q] / BM) * (tb.N[q] / BN);
+  }
+  for (int q = tb.nprob; q <= kWgradMaxProblems; ++q) tb.tile0[q] = tiles;
+  kern<<<tiles, NTHREADS, smem, s>>>(tb, K);
   return hipGetLastError();
 }
 
-// wgrad launch (one pair, or g.group pairs); *taken stays false if the shape is not one for the MFMA kernel
-static hipError_t launch_wgrad(const GemmArgs& g, hipStream_t s, bool* taken) {
-  const int ngroup = g.group >= 2 ? g.group : 1;
-  if (g.epilogue != EPI_ACCUM_F32 || ngroup > kGemmGroupMax) return hipSuccess;
-  if (!(g.a_sm == 1 && g.b_sn == 1) || g.a_sk == 1 || g.b_sk == 1) return hipSuccess;
-  const long lda = g.a_sk, ldb = g.b_sk;
-  if (g.M % 128 != 0 || g.N % BN != 0 || g.K % 64 != 0 || lda % 8 != 0 || ldb % 8 != 0 || !aligned16(g.outf))
+}  // namespace
+
+template <typename T> hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s, bool* taken) {
+  *taken = false;
+  return hipSuccess;
+}
+
+// wgrad launch for the gradients of one W pass; *taken stays false if a shape is not one for the MFMA kernel
+template <typename T> hipError_t launch_wgrad_multi_mfma(const WgradMultiArgs& w, hipStream_t s, bool* taken) {
+  *taken = false;
+  return hipSuccess;
+}
+template <> hipError_t launch_wgrad_multi_mfma<bf16_t>(const WgradMultiArgs& w, hipStream_t s, bool* taken) {
+  *taken = false;
+  if (w.nprob < 1 || w.nprob > kWgradMaxProblems || w.ngroup < 1 || w.ngroup > kGemmGroupMax ||
+      w.nprob * w.ngroup > kWgradMaxPairs || w.K <= 0 || w.K % 64 != 0)
     return hipSuccess;
-  GroupPtrs gp;
-  for (int i = 0; i < kGemmGroupMax; ++i) {
-    gp.a[i] = (const bf16_t*)(g.group >= 2 ? g.group_a[i < ngroup ? i : 0] : g.A);
-    gp.b[i] = (const bf16_t*)(g.group >= 2 ? g.group_b[i < ngroup ? i : 0] : g.B);
-    if (!gp.a[i] || !gp.b[i] || !aligned16(gp.a[i]) || !aligned16(gp.b[i])) return hipSuccess;
+  WgradTable tb{};
+  tb.nprob = w.nprob;
+  tb.ngroup = w.ngroup;
+  bool all256 = true;
+  long t256 = 0, t128 = 0;
+  for (int q = 0; q < w.nprob; ++q) {
+    const int M = w.M[q], N = w.N[q];
+    if (M <= 0 || N <= 0 || M % 128 != 0 || N % BN != 0 || !aligned16(w.outf[q])) return hipSuccess;
+    tb.M[q] = M; tb.N[q] = N; tb.outf[q] = w.outf[q];
+    all256 = all256 && M % 256 == 0;
+    t256 += (long)(M / 256) * (N / BN);
+    t128 += (long)(M / 128) * (N / BN);
+    for (int g = 0; g < w.ngroup; ++g) {
+      const void* a = w.a[q * w.ngroup + g];
+      const void* b = w.b[q * w.ngroup + g];
+      if (!a || !b || !aligned16(a) || !aligned16(b)) return hipSuccess;
+      tb.a[q * w.ngroup + g] = (const bf16_t*)a;
+      tb.b[q * w.ngroup + g] = (const bf16_t*)b;
+    }
   }
+  if (t128 >= (1L << 30)) return hipSuccess;
   *taken = true;
   // 256-row tiles (one workgroup per CU, four-stage ring) when they fill most of the chip; else 128-row
   // tiles, two workgroups per CU with a three-stage ring if there are more tiles than CUs, one with a
   // five-stage ring otherwise.  The choice does not change the result (see the kernel).
-  const long t256 = g.M % 256 == 0 ? (long)(g.M / 256) * (g.N / BN) : 0;
-  const long t128 = (long)(g.M / 128) * (g.N / BN);
-  if (t256 >= 192) return run_wgrad<256, 4, true>(gp, g, ngroup, lda, ldb, s);
-  if (t128 > 256) return run_wgrad<128, 3, true>(gp, g, ngroup, lda, ldb, s);
-  return run_wgrad<128, 5, true>(gp, g, ngroup, lda, ldb, s);
+  if (all256 && t256 >= 192) return run_wgrad<256, 4, true>(tb, w.K, s);
+  if (t128 > 256) return run_wgrad<128, 3, true>(tb, w.K, s);
+  return run_wgrad<128, 5, true>(tb, w.K, s);
 }
+template hipError_t launch_wgrad_multi_mfma<float>(const WgradMultiArgs&, hipStream_t, bool*);
+
+namespace {
+
+// one accumulate GEMM (one pair, or g.group pairs) through the same kernel
+hipError_t launch_wgrad(const GemmArgs& g, hipStream_t s, bool* taken) {
+  const int ngroup = g.group >= 2 ? g.group : 1;
+  if (g.epilogue != EPI_ACCUM_F32 || ngroup > kGemmGroupMax) return hipSuccess;
+  if (!(g.a_sm == 1 && g.b_sn == 1) || g.a_sk != g.M || g.b_sk != g.N) return hipSuccess;
+  WgradMultiArgs w{};
+  w.nprob = 1; w.ngroup = ngroup; w.K = g.K;
+  w.M[0] = g.M; w.N[0] = g.N; w.outf[0] = g.outf;
+  for (int i = 0; i < ngroup; ++i) {
+    w.a[i] = g.group >= 2 ? g.group_a[i] : g.A;
+    w.b[i] = g.group >= 2 ? g.group_b[i] : g.B;
+  }
+  return launch_wgrad_multi_mfma<bf16_t>(w, s, taken);
+}
+
+}  // namespace
 
 template <> hipError_t launch_gemm_mfma<bf16_t>(const GemmArgs& g, hipStream_t s, bool* taken) {
   *taken = false;

@@ -476,41 +476,75 @@ template <typename T> struct Exec {
     return ZB_OK;
   }
 
-  static zb_status backward_weight(zb_stage* st, int mb, int l_hi = -1, int l_lo = 0) {
+  // W of n microbatches (1 <= n <= kGemmGroupMax, all of one chunk) for layers l_hi .. l_lo: the accumulate
+  // GEMMs of as many whole layers as one launch takes (tiles of equal duration, so the partly filled last
+  // round of workgroups is paid once per launch, not once per weight matrix), each summing its n operand
+  // pairs in the order given; then the bias column sums, layer by layer and microbatch by microbatch in the
+  // same order.
+  static zb_status wgrad_layers(zb_stage* st, const int* mbs, int n, int l_hi, int l_lo) {
     const int h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
-    char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
-    char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
     const double E = sizeof(T);
-    int bottom, top;
-    layer_range(st, mb, &bottom, &top);
-    if (l_hi < 0) { l_hi = top; l_lo = bottom; }
-    for (int l = l_hi; l >= l_lo; --l) {
+    int bottom, top;  // the same for every microbatch given (the caller splits at chunk changes)
+    layer_range(st, mbs[0], &bottom, &top);
+    struct Lin { size_t fw_off, bw_off; bool top_dy; int kin, nout, wi, bi; };
+    auto lins_of = [&](int l, Lin (&lins)[4]) {
       const LayerOff& q = st->lo[l];
-      const T* dyl = l == top ? (const T*)(st->in_dy + st->act_bytes * (size_t)mb) : (const T*)(bw + q.bw_dy);
-      struct Pair { const T* x; const T* dy; int kin, nout, wi, bi; };
-      const Pair pairs[4] = {
-          {(const T*)(fw + q.fw_g), dyl, f, h, ZB_P_W2, ZB_P_B2},
-          {(const T*)(fw + q.fw_u), (const T*)(bw + q.bw_dfh), h, f, ZB_P_W1, ZB_P_B1},
-          {(const T*)(fw + q.fw_c), (const T*)(bw + q.bw_dy1), h, h, ZB_P_WO, ZB_P_BO},
-          {(const T*)(fw + q.fw_a), (const T*)(bw + q.bw_dqkv), h, 3 * h, ZB_P_WQKV, ZB_P_BQKV}};
-      for (const Pair& pr : pairs) {
-        GemmArgs g{};  // dW[kin, nout] += X^T dY
-        g.A = pr.x; g.B = pr.dy; g.M = pr.kin; g.N = pr.nout; g.K = T_;
-        g.a_sm = 1; g.a_sk = pr.kin; g.b_sk = pr.nout; g.b_sn = 1;
-        g.epilogue = EPI_ACCUM_F32; g.outf = st->G(l, pr.wi);
-        ZB_HIP(st, gemm(st, KC_GEMM_WGRAD, g));
+      lins[0] = {q.fw_g, q.bw_dy, l == top, f, h, ZB_P_W2, ZB_P_B2};
+      lins[1] = {q.fw_u, q.bw_dfh, false, h, f, ZB_P_W1, ZB_P_B1};
+      lins[2] = {q.fw_c, q.bw_dy1, false, h, h, ZB_P_WO, ZB_P_BO};
+      lins[3] = {q.fw_a, q.bw_dqkv, false, h, 3 * h, ZB_P_WQKV, ZB_P_BQKV};
+    };
+    auto dy_of = [&](const Lin& ln, int mb) -> const char* {
+      const char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
+      return ln.top_dy ? (const char*)(st->in_dy + st->act_bytes * (size_t)mb) : bw + ln.bw_off;
+    };
+    int per_launch = kWgradMaxPairs / (4 * n);  // whole layers per launch
+    if (per_launch > kWgradMaxProblems / 4) per_launch = kWgradMaxProblems / 4;
+    if (per_launch < 1) per_launch = 1;
+    for (int l1 = l_hi; l1 >= l_lo; l1 -= per_launch) {
+      const int l0 = l1 - per_launch + 1 > l_lo ? l1 - per_launch + 1 : l_lo;
+      WgradMultiArgs w{};
+      w.ngroup = n; w.K = T_;
+      double flops = 0, bytes = 0;
+      for (int l = l1; l >= l0; --l) {
+        Lin lins[4];
+        lins_of(l, lins);
+        for (const Lin& ln : lins) {
+          const int q = w.nprob++;
+          w.M[q] = ln.kin; w.N[q] = ln.nout; w.outf[q] = st->G(l, ln.wi);
+          for (int i = 0; i < n; ++i) {
+            const char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mbs[i]];
+            w.a[q * n + i] = fw + ln.fw_off;
+            w.b[q * n + i] = dy_of(ln, mbs[i]);
+          }
+          flops += 2.0 * ln.kin * ln.nout * T_ * n;
+          bytes += 8.0 * ln.kin * ln.nout + E * (double)T_ * ((double)ln.kin + ln.nout) * n;
+        }
       }
-      {  // the four bias gradients: column sums of the same dY's
+      {
+        ProfScope ps(st, KC_GEMM_WGRAD, flops, bytes);
+        ZB_HIP(st, launch_wgrad_multi<T>(w, s));
+      }
+    }
+    for (int l = l_hi; l >= l_lo; --l) {
+      Lin lins[4];
+      lins_of(l, lins);
+      for (int i = 0; i < n; ++i) {  // the four bias gradients: column sums of the same dY's
         const void* dys[4];
         float* dbs[4];
         int ns[4];
-        for (int q = 0; q < 4; ++q) { dys[q] = pairs[q].dy; dbs[q] = st->G(l, pairs[q].bi); ns[q] = pairs[q].nout; }
+        for (int q = 0; q < 4; ++q) { dys[q] = dy_of(lins[q], mbs[i]); dbs[q] = st->G(l, lins[q].bi); ns[q] = lins[q].nout; }
         ProfScope ps(st, KC_COLSUM, 0, E * T_ * (double)(ns[0] + ns[1] + ns[2] + ns[3]));
         ZB_HIP(st, launch_colsum_accum_multi<T>(dys, dbs, ns, 4, st->ln_partials, T_, s));
       }
     }
     return ZB_OK;
+  }
+
+  static zb_status backward_weight(zb_stage* st, int mb, int l_hi = -1, int l_lo = 0) {
+    if (l_hi < 0) layer_range(st, mb, &l_lo, &l_hi);
+    return wgrad_layers(st, &mb, 1, l_hi, l_lo);
   }
 
   // The traditional single backward (Sec. 1): layer by layer, the input gradient and right after it the
@@ -526,57 +560,11 @@ template <typename T> struct Exec {
     return ZB_OK;
   }
 
-  // W of n microbatches (2 <= n <= kGemmGroupMax), parameter by parameter: one grouped wgrad GEMM per
-  // weight matrix, then the bias column sums microbatch by microbatch in the same order.
+  // W of n microbatches (2 <= n <= kGemmGroupMax) of one chunk: every gradient is read and written once.
   static zb_status backward_weight_group(zb_stage* st, const int* mbs, int n) {
-    const int h = st->h, f = st->ffn, T_ = st->T;
-    hipStream_t s = st->stream;
-    const double E = sizeof(T);
-    int bottom, top;  // the same for every member of the group (the caller splits groups at chunk changes)
+    int bottom, top;
     layer_range(st, mbs[0], &bottom, &top);
-    for (int l = top; l >= bottom; --l) {
-      const LayerOff& q = st->lo[l];
-      struct Lin { size_t fw_off, bw_off; bool top_dy; int kin, nout, wi, bi; };
-      const Lin lins[4] = {{q.fw_g, q.bw_dy, l == top, f, h, ZB_P_W2, ZB_P_B2},
-                           {q.fw_u, q.bw_dfh, false, h, f, ZB_P_W1, ZB_P_B1},
-                           {q.fw_c, q.bw_dy1, false, h, h, ZB_P_WO, ZB_P_BO},
-                           {q.fw_a, q.bw_dqkv, false, h, 3 * h, ZB_P_WQKV, ZB_P_BQKV}};
-      for (const Lin& ln : lins) {
-        GemmArgs g{};  // dW[kin, nout] += sum over the group of X^T dY, one product after the other
-        g.M = ln.kin; g.N = ln.nout; g.K = T_;
-        g.a_sm = 1; g.a_sk = ln.kin; g.b_sk = ln.nout; g.b_sn = 1;
-        g.epilogue = EPI_ACCUM_F32; g.outf = st->G(l, ln.wi);
-        g.group = n;
-        for (int i = 0; i < n; ++i) {
-          const int mb = mbs[i];
-          const char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
-          const char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
-          g.group_a[i] = fw + ln.fw_off;
-          g.group_b[i] = ln.top_dy ? (const char*)(st->in_dy + st->act_bytes * (size_t)mb) : bw + ln.bw_off;
-        }
-        g.A = g.group_a[0]; g.B = g.group_b[0];
-        {
-          ProfScope ps(st, KC_GEMM_WGRAD, 2.0 * g.M * g.N * g.K * n,
-                       8.0 * g.M * g.N + E * (double)g.K * ((double)g.M + g.N) * n);
-          ZB_HIP(st, launch_gemm<T>(g, s));
-        }
-      }
-      for (int i = 0; i < n; ++i) {  // bias gradients, microbatch by microbatch in the group's order
-        const int mb = mbs[i];
-        const char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
-        const void* dys[4];
-        float* dbs[4];
-        int ns[4];
-        for (int q = 0; q < 4; ++q) {
-          dys[q] = lins[q].top_dy ? (const char*)(st->in_dy + st->act_bytes * (size_t)mb) : bw + lins[q].bw_off;
-          dbs[q] = st->G(l, lins[q].bi);
-          ns[q] = lins[q].nout;
-        }
-        ProfScope ps(st, KC_COLSUM, 0, E * T_ * (double)(ns[0] + ns[1] + ns[2] + ns[3]));
-        ZB_HIP(st, launch_colsum_accum_multi<T>(dys, dbs, ns, 4, st->ln_partials, T_, s));
-      }
-    }
-    return ZB_OK;
+    return wgrad_layers(st, mbs, n, top, bottom);
   }
 };
 

@@ -75,8 +75,8 @@ struct GemmArgs {
   float* workspace;    // optional fp32 scratch for split-K partial products (device), may be null
   size_t workspace_floats;
   // Grouped wgrad (EPI_ACCUM_F32 only): group >= 2 operand pairs of the same shape and strides;
-  // outf = (((outf + A_0^T B_0) + A_1^T B_1) + ...), each product rounded to fp32 before it is added,
-  // i.e. bit for bit what `group` separate launches give.  A and B above are ignored then.
+  // outf += A_0^T B_0, then += A_1^T B_1, ...: bit for bit what `group` separate launches give (whichever
+  // kernel takes the shape).  A and B above are ignored then.
   int group;
   const void* group_a[16];
   const void* group_b[16];
@@ -84,6 +84,19 @@ struct GemmArgs {
 constexpr int kGemmGroupMax = 16;
 
 template <typename T> hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+
+// The accumulate GEMMs of one W pass in one launch: dW[q] (fp32 [M[q], N[q]], row stride N[q]) +=
+// sum over g < ngroup of X[q][g]^T dY[q][g], X [K, M[q]] and dY [K, N[q]] of type T, dense, for q < nprob.
+// Every dW[q] gets exactly the bits that launch_gemm gives it problem by problem.
+constexpr int kWgradMaxProblems = 16, kWgradMaxPairs = 64;
+struct WgradMultiArgs {
+  int nprob, ngroup, K;  // nprob * ngroup <= kWgradMaxPairs, ngroup <= kGemmGroupMax
+  int M[kWgradMaxProblems], N[kWgradMaxProblems];
+  float* outf[kWgradMaxProblems];
+  const void* a[kWgradMaxPairs];  // pair g of problem q at [q * ngroup + g]
+  const void* b[kWgradMaxPairs];
+};
+template <typename T> hipError_t launch_wgrad_multi(const WgradMultiArgs& w, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // attention (causal, per head), token-major QKV [tokens, 3h] with columns [Q|K|V] head-major
