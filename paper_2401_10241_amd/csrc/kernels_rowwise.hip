@@ -233,45 +233,10 @@ __global__ __launch_bounds__(256) void layernorm_bwd_reduce_kernel(const float* 
   }
 }
 
-// Bias gradient, stage 1: column sums of one slice of rows.  256 threads = 16 column-lanes (each kV
-// consecutive columns) x 16 row groups; grid.y = row slices; out[slice][n].
-template <typename T, int kV>
-__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __restrict__ dy, float* __restrict__ out,
-                                                                  int rows, int n, int rows_per_slice) {
-  __shared__ float red[16][16 * kV + 1];
-  const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
-  const int col = (blockIdx.x * 16 + cl) * kV;
-  const int r_begin = blockIdx.y * rows_per_slice;
-  const int r_end = min(rows, r_begin + rows_per_slice);
-  float acc[kV];
-#pragma unroll
-  for (int e = 0; e < kV; ++e) acc[e] = 0.f;
-  if (col < n) {
-    for (int r = r_begin + rg; r < r_end; r += 16) {
-      const T* p = dy + (size_t)r * n + col;
-#pragma unroll
-      for (int e = 0; e < kV; e += 4) {
-        float v[4];
-        Vec4<T>::load(p + e, v);
-        acc[e] += v[0]; acc[e + 1] += v[1]; acc[e + 2] += v[2]; acc[e + 3] += v[3];
-      }
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < kV; ++e) red[rg][cl * kV + e] = acc[e];
-  __syncthreads();
-  if (threadIdx.x < 16 * kV) {
-    const int c = blockIdx.x * 16 * kV + threadIdx.x;
-    if (c < n) {
-      float t = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) t += red[r][threadIdx.x];
-      out[(size_t)blockIdx.y * n + c] = t;
-    }
-  }
-}
-// The same for up to four matrices of one row count in one launch (the four dY of a layer's W pass):
-// column blocks of the matrices are laid side by side, out[slice][total columns].
+// Bias gradients: column sums of up to four matrices of one row count in one launch pair (the four dY of a
+// layer's W pass).  Stage 1: column sums of one slice of rows; 256 threads = 16 column-lanes (each kV
+// consecutive columns) x 16 row groups; grid.y = row slices; column blocks of the matrices are laid side
+// by side, out[slice][total columns].
 template <typename T, int kV>
 __global__ __launch_bounds__(kThreads) void colsum_partial_multi_kernel(ColsumSegs sg, float* __restrict__ out,
                                                                         int rows, int rows_per_slice) {
@@ -313,6 +278,7 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_multi_kernel(ColsumSe
     }
   }
 }
+// stage 2: db[c] += slices added in order
 __global__ void colsum_final_multi_kernel(ColsumSegs sg, const float* __restrict__ part, int slices) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= sg.total) return;
@@ -322,14 +288,6 @@ __global__ void colsum_final_multi_kernel(ColsumSegs sg, const float* __restrict
   float t = 0.f;
   for (int k = 0; k < slices; ++k) t += part[(size_t)k * sg.total + c];
   sg.db[seg][c - sg.col0[seg]] += t;
-}
-// stage 2: db[c] += slices added in order
-__global__ void colsum_final_kernel(const float* __restrict__ part, float* __restrict__ db, int slices, int n) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= n) return;
-  float t = 0.f;
-  for (int k = 0; k < slices; ++k) t += part[(size_t)k * n + c];
-  db[c] += t;
 }
 
 // dst[c][r] = src[r][c] for a [rows][cols] bf16 matrix; 64 x 64 tiles through LDS
@@ -455,20 +413,6 @@ hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, cons
 }
 
 template <typename T>
-hipError_t launch_colsum_accum(const T* dy, float* db, float* scratch, int rows, int n, hipStream_t s) {
-  constexpr int kV = 16 / sizeof(T);
-  if (n % kV != 0 || rows <= 0) return hipErrorInvalidValue;
-  const int slices = rows >= 8 * 16 ? kColsumSlices : 1;
-  const int per_block = 16 * kV;
-  dim3 grid((n + per_block - 1) / per_block, slices);
-  colsum_partial_kernel<T, kV><<<grid, kThreads, 0, s>>>(dy, scratch, rows, n, (rows + slices - 1) / slices);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  colsum_final_kernel<<<(n + 255) / 256, 256, 0, s>>>(scratch, db, slices, n);
-  return hipGetLastError();
-}
-
-template <typename T>
 hipError_t launch_colsum_accum_multi(const void* const* dy, float* const* db, const int* n, int count, float* scratch,
                                      int rows, hipStream_t s) {
   constexpr int kV = 16 / sizeof(T);
@@ -535,7 +479,6 @@ template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStr
                                               hipStream_t);                                                      \
   template hipError_t launch_layernorm_bwd<T>(const T*, const T*, const float*, const float*, const T*, T*,      \
                                               float*, float*, float*, int, int, hipStream_t);                    \
-  template hipError_t launch_colsum_accum<T>(const T*, float*, float*, int, int, hipStream_t);                   \
   template hipError_t launch_colsum_accum_multi<T>(const void* const*, float* const*, const int*, int, float*,  \
                                                    int, hipStream_t);                                           \
   template hipError_t launch_convert_from_f32<T>(const float*, T*, size_t, hipStream_t);                         \

@@ -128,12 +128,9 @@ hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, cons
                                 hipStream_t s);
 constexpr int kLnBwdSlices = 16;
 
-// bias gradient: db[n] += sum_rows dy[r, n]; scratch holds kColsumSlices * n floats
+// bias gradients: db[q][c] += sum_rows dy[q][r, c] for `count` <= 4 matrices dy[q] of [rows, n[q]] in one launch
+// pair; row slices are added in a fixed order; scratch holds kColsumSlices * (n[0] + ... + n[count-1]) floats
 constexpr int kColsumSlices = 8;
-template <typename T>
-hipError_t launch_colsum_accum(const T* dy, float* db, float* scratch, int rows, int n, hipStream_t s);
-// the same for `count` <= 4 matrices dy[q] of [rows, n[q]] in one launch pair; every db[q][c] gets exactly the
-// sum the single call gives it; scratch holds kColsumSlices * (n[0] + ... + n[count-1]) floats
 struct ColsumSegs {
   const void* dy[4];
   float* db[4];
