@@ -81,8 +81,9 @@ constexpr int kWaitVm0 = 0 | (7 << 4) | (15 << 8);  // s_waitcnt vmcnt(0) only
 // its own L2); all row blocks of one head are sent to the same XCD so that the head's K/V (or Q/dO) tiles
 // are fetched into one L2 only.  `first_heavy`: row blocks in descending order (the last query block has
 // the most keys); otherwise ascending (key block 0 sees the most queries).
-__device__ __forceinline__ void map_block(int nrb, int a, int b, bool first_heavy, int* rb, int* head, int* bi) {
-  const int id = blockIdx.x, heads = a * b;
+__device__ __forceinline__ void map_block(int id, int nrb, int a, int b, bool first_heavy, int* rb, int* head,
+                                          int* bi) {
+  const int heads = a * b;
   int hl, r;
   if ((heads & 7) == 0) {
     // within an XCD: heaviest row blocks of all its heads first, so the light ones fill the tail
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
   bf16_t* sV = sK + 2 * TILE;                        // [2][TILE]
   int qb, head, bi;
-  map_block(s / QB, a, gridDim.x / (a * (s / QB)), true, &qb, &head, &bi);  // heaviest blocks first
+  map_block(blockIdx.x, s / QB, a, gridDim.x / (a * (s / QB)), true, &qb, &head, &bi);  // heaviest blocks first
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
@@ -235,16 +236,14 @@ __global__ __launch_bounds__(64) void attn_bwd128_prep_kernel(const bf16_t* __re
 // backward, dQ: workgroup = 128 queries, loop over key tiles up to the diagonal (same pipeline as forward)
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bwd128_dq_kernel(const bf16_t* __restrict__ qkv,
-                                                             const bf16_t* __restrict__ dout,
-                                                             const float* __restrict__ lse,
-                                                             const float* __restrict__ dvec,
-                                                             bf16_t* __restrict__ dqkv, int s, int a, float scale) {
-  extern __shared__ __align__(1024) unsigned char smem_raw[];
+__device__ __forceinline__ void attn_bwd128_dq_body(unsigned char* smem_raw, int id, int nb,
+                                                    const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                    const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                    bf16_t* __restrict__ dqkv, int s, int a, float scale) {
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
   bf16_t* sV = sK + 2 * TILE;                        // [2][TILE]
   int qb, head, bi;
-  map_block(s / QB, a, gridDim.x / (a * (s / QB)), true, &qb, &head, &bi);
+  map_block(id, s / QB, a, nb, true, &qb, &head, &bi);
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
@@ -348,17 +347,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd128_dq_kernel(const bf16_t* __
 // wave has the same number of loads in flight).
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd128_dkv_kernel(const bf16_t* __restrict__ qkv,
-                                                              const bf16_t* __restrict__ dout,
-                                                              const float* __restrict__ lse,
-                                                              const float* __restrict__ dvec,
-                                                              bf16_t* __restrict__ dqkv, int s, int a, float scale) {
-  extern __shared__ __align__(1024) unsigned char smem_raw[];
+__device__ __forceinline__ void attn_bwd128_dkv_body(unsigned char* smem_raw, int id, int nb,
+                                                     const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                     const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                     bf16_t* __restrict__ dqkv, int s, int a, float scale) {
   bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [3][TILE]
   bf16_t* sO = sQ + 3 * TILE;                        // [3][TILE]  dO tiles
   float* sS = reinterpret_cast<float*>(sO + 3 * TILE);  // [3][4][64]: lse, D, spare, spare
   int kb, head, bi;
-  map_block(s / QB, a, gridDim.x / (a * (s / QB)), false, &kb, &head, &bi);  // key block 0 has the most work
+  map_block(id, s / QB, a, nb, false, &kb, &head, &bi);  // key block 0 has the most work
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
@@ -472,6 +469,22 @@ __global__ __launch_bounds__(256) void attn_bwd128_dkv_kernel(const bf16_t* __re
     }
 }
 
+// dK/dV and dQ in one launch: they are independent (both recompute S), and their workgroups have very
+// uneven lengths (causal: 1 to 16 tiles), so the dQ workgroups fill the CUs that the shorter dK/dV
+// workgroups leave early.  The first half of the grid is dK/dV (one workgroup per CU: it holds K, V and both
+// accumulators in registers), heaviest key blocks first; the second half dQ, heaviest query blocks first.
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd128_kernel(const bf16_t* __restrict__ qkv,
+                                                          const bf16_t* __restrict__ dout,
+                                                          const float* __restrict__ lse,
+                                                          const float* __restrict__ dvec,
+                                                          bf16_t* __restrict__ dqkv, int s, int a, int nb, float scale) {
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  const int per = gridDim.x >> 1;
+  if ((int)blockIdx.x < per) attn_bwd128_dkv_body<D>(smem_raw, blockIdx.x, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+  else attn_bwd128_dq_body<D>(smem_raw, blockIdx.x - per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+}
+
 template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
   constexpr size_t smem = (size_t)4 * TILE * sizeof(bf16_t);
@@ -491,12 +504,10 @@ template <int D> hipError_t run_bwd_dma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
   constexpr size_t smem_q = (size_t)4 * TILE * sizeof(bf16_t);
   constexpr size_t smem_kv = (size_t)6 * TILE * sizeof(bf16_t) + 3 * 4 * 64 * sizeof(float);
+  constexpr size_t smem = smem_kv > smem_q ? smem_kv : smem_q;
   if (!done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dq_kernel<D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_q);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_dkv_kernel<D>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_kv);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     done = true;
   }
@@ -505,13 +516,9 @@ template <int D> hipError_t run_bwd_dma(const AttnArgs& a, hipStream_t s) {
   attn_bwd128_prep_kernel<D><<<grid1, 64, 0, s>>>((const bf16_t*)a.o, (const bf16_t*)a.dout, a.dvec, a.s, a.a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  dim3 grid((a.s / QB) * a.a * a.b);
-  attn_bwd128_dq_kernel<D><<<grid, 256, smem_q, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
-                                                     (bf16_t*)a.dqkv, a.s, a.a, scale);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  attn_bwd128_dkv_kernel<D><<<grid, 256, smem_kv, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
-                                                       (bf16_t*)a.dqkv, a.s, a.a, scale);
+  const int per = (a.s / QB) * a.a * a.b;
+  attn_bwd128_kernel<D><<<2 * per, 256, smem, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
+                                                   (bf16_t*)a.dqkv, a.s, a.a, a.b, scale);
   return hipGetLastError();
 }
 
