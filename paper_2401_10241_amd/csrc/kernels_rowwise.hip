@@ -114,13 +114,11 @@ __device__ __forceinline__ void block_sum2(float& a, float& b, float (*red)[2]) 
 // dx of one row per workgroup: dx = resid + rstd * (g*gamma - mean(g*gamma) - xhat * mean(g*gamma*xhat)).
 // NCH = ceil(h / 1024) chunks of 4 per lane; the whole row stays in registers between the two passes.
 template <typename T, int NCH>
-__global__ __launch_bounds__(kThreads) void layernorm_bwd_dx_kernel(const T* __restrict__ g, const T* __restrict__ x,
-                                                                    const float* __restrict__ stats,
-                                                                    const float* __restrict__ gamma,
-                                                                    const T* __restrict__ resid, T* __restrict__ dx,
-                                                                    int h) {
+__device__ __forceinline__ void layernorm_bwd_dx_body(int row, const T* __restrict__ g, const T* __restrict__ x,
+                                                      const float* __restrict__ stats,
+                                                      const float* __restrict__ gamma, const T* __restrict__ resid,
+                                                      T* __restrict__ dx, int h) {
   __shared__ float red[4][2];
-  const int row = blockIdx.x;
   const size_t off = (size_t)row * h;
   const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
   float gg[NCH][kVec], xh[NCH][kVec], rr[NCH][kVec];
@@ -160,15 +158,14 @@ __global__ __launch_bounds__(kThreads) void layernorm_bwd_dx_kernel(const T* __r
 // Column sums of g*xhat and g over one slice of rows: partials[slice][0][h] and partials[slice][1][h].
 // 256 threads = 16 column-lanes (8 consecutive columns each) x 16 row groups; grid.y = row slices.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void layernorm_bwd_param_kernel(const T* __restrict__ g,
-                                                                       const T* __restrict__ x,
-                                                                       const float* __restrict__ stats,
-                                                                       float* __restrict__ partials, int rows, int h,
-                                                                       int rows_per_slice) {
+__device__ __forceinline__ void layernorm_bwd_param_body(int bx, int by, const T* __restrict__ g,
+                                                         const T* __restrict__ x, const float* __restrict__ stats,
+                                                         float* __restrict__ partials, int rows, int h,
+                                                         int rows_per_slice) {
   __shared__ float red[2][16][129];
   const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
-  const int col = (blockIdx.x * 16 + cl) * 8;
-  const int r_begin = blockIdx.y * rows_per_slice;
+  const int col = (bx * 16 + cl) * 8;
+  const int r_begin = by * rows_per_slice;
   const int r_end = min(rows, r_begin + rows_per_slice);
   float ag[8], ab[8];
 #pragma unroll
@@ -197,12 +194,30 @@ __global__ __launch_bounds__(kThreads) void layernorm_bwd_param_kernel(const T* 
   }
   __syncthreads();
   const int which = threadIdx.x >> 7, t = threadIdx.x & 127;
-  const int c = blockIdx.x * 128 + t;
+  const int c = bx * 128 + t;
   if (c < h) {
     float sum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sum += red[which][r][t];
-    partials[((size_t)blockIdx.y * 2 + which) * h + c] = sum;
+    partials[((size_t)by * 2 + which) * h + c] = sum;
+  }
+}
+
+// One launch for both: workgroups 0 .. rows-1 compute dx of one row each, the rest the gamma / beta partial
+// sums (column block bx, row slice by).  Nothing downstream waits for the partial sums, so they ride along
+// with the dx rows instead of taking a launch of their own.
+template <typename T, int NCH>
+__global__ __launch_bounds__(kThreads) void layernorm_bwd_kernel(const T* __restrict__ g, const T* __restrict__ x,
+                                                                 const float* __restrict__ stats,
+                                                                 const float* __restrict__ gamma,
+                                                                 const T* __restrict__ resid, T* __restrict__ dx,
+                                                                 float* __restrict__ partials, int rows, int h,
+                                                                 int rows_per_slice, int col_blocks) {
+  if ((int)blockIdx.x < rows) {
+    layernorm_bwd_dx_body<T, NCH>(blockIdx.x, g, x, stats, gamma, resid, dx, h);
+  } else {
+    const int q = blockIdx.x - rows;
+    layernorm_bwd_param_body<T>(q % col_blocks, q / col_blocks, g, x, stats, partials, rows, h, rows_per_slice);
   }
 }
 
@@ -378,9 +393,11 @@ hipError_t launch_layernorm_fwd(const T* x, const float* gamma, const float* bet
 }
 
 template <typename T, int NCH>
-hipError_t run_ln_bwd_dx(const T* g, const T* x, const float* stats, const float* gamma, const T* resid, T* dx,
-                         int rows, int h, hipStream_t s) {
-  layernorm_bwd_dx_kernel<T, NCH><<<rows, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, h);
+hipError_t run_ln_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid, T* dx,
+                      float* partials, int rows, int h, int slices, hipStream_t s) {
+  const int rows_per_slice = (rows + slices - 1) / slices, col_blocks = (h + 127) / 128;
+  layernorm_bwd_kernel<T, NCH><<<rows + col_blocks * slices, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, partials,
+                                                                             rows, h, rows_per_slice, col_blocks);
   return hipGetLastError();
 }
 
@@ -390,24 +407,20 @@ hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, cons
                                 hipStream_t s) {
   if (h % kVec != 0 || h > kThreads * kVec * kMaxChunks || rows <= 0) return hipErrorInvalidValue;
   const int nch = (h + kThreads * kVec - 1) / (kThreads * kVec);
-  hipError_t e;
-  switch (nch) {
-    case 1: e = run_ln_bwd_dx<T, 1>(g, x, stats, gamma, resid, dx, rows, h, s); break;
-    case 2: e = run_ln_bwd_dx<T, 2>(g, x, stats, gamma, resid, dx, rows, h, s); break;
-    case 3: e = run_ln_bwd_dx<T, 3>(g, x, stats, gamma, resid, dx, rows, h, s); break;
-    case 4: e = run_ln_bwd_dx<T, 4>(g, x, stats, gamma, resid, dx, rows, h, s); break;
-    case 5: e = run_ln_bwd_dx<T, 5>(g, x, stats, gamma, resid, dx, rows, h, s); break;
-    case 6: e = run_ln_bwd_dx<T, 6>(g, x, stats, gamma, resid, dx, rows, h, s); break;
-    default: e = run_ln_bwd_dx<T, 8>(g, x, stats, gamma, resid, dx, rows, h, s); break;
-  }
-  if (e != hipSuccess) return e;
   // gamma / beta gradients: row slices of at least 16 rows, at most kLnBwdSlices of them
   int slices = (rows + 15) / 16;
   if (slices > kLnBwdSlices) slices = kLnBwdSlices;
-  const int rows_per_slice = (rows + slices - 1) / slices;
-  layernorm_bwd_param_kernel<T><<<dim3((h + 127) / 128, slices), kThreads, 0, s>>>(g, x, stats, partials, rows, h,
-                                                                                  rows_per_slice);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipError_t e;
+  switch (nch) {
+    case 1: e = run_ln_bwd<T, 1>(g, x, stats, gamma, resid, dx, partials, rows, h, slices, s); break;
+    case 2: e = run_ln_bwd<T, 2>(g, x, stats, gamma, resid, dx, partials, rows, h, slices, s); break;
+    case 3: e = run_ln_bwd<T, 3>(g, x, stats, gamma, resid, dx, partials, rows, h, slices, s); break;
+    case 4: e = run_ln_bwd<T, 4>(g, x, stats, gamma, resid, dx, partials, rows, h, slices, s); break;
+    case 5: e = run_ln_bwd<T, 5>(g, x, stats, gamma, resid, dx, partials, rows, h, slices, s); break;
+    case 6: e = run_ln_bwd<T, 6>(g, x, stats, gamma, resid, dx, partials, rows, h, slices, s); break;
+    default: e = run_ln_bwd<T, 8>(g, x, stats, gamma, resid, dx, partials, rows, h, slices, s); break;
+  }
+  if (e != hipSuccess) return e;
   layernorm_bwd_reduce_kernel<<<(h + 63) / 64, 256, 0, s>>>(partials, dgamma, dbeta, slices, h);
   return hipGetLastError();
 }
