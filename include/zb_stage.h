@@ -251,6 +251,23 @@ typedef struct {
  * predicates.  report may be NULL (then the call does not wait for the device). */
 zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, zb_step_report* report);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the first step of zb_optimizer_step_validated, the squared norm and the
+ * non-finite flag of a gradient vector, with the partial sums of its reduction levels in a fixed array
+ * inside the library (about 12.6 MB per GPU, held until the process ends) instead of a stage's arena.
+ *   grads          device, n floats, 16-byte aligned; n > 0, n % 4 == 0, n <= ZB_GRAD_NORM_STATIC_MAX_FLOATS
+ *   sq_out         device, one double: sum of squares, accumulated in fp64 in the same fixed order as
+ *                  zb_step_report.local_sq (bit-identical for the same n and values)
+ *   nonfinite_out  device, one int32: 1 if any element is NaN or Inf, else 0
+ *   hip_stream     hipStream_t or NULL; the call only enqueues kernels (no synchronisation, no memset,
+ *                  no hipMalloc / hipFree), so it may be captured into a graph
+ * ZB_EINVAL for null pointers, misaligned grads or n outside the range above (nothing is launched then);
+ * ZB_EDEVICE if a HIP call fails.  All calls on one GPU share the array: calls that overlap on one GPU
+ * (different streams without ordering between them) race; calls on one stream are safe. */
+#define ZB_GRAD_NORM_STATIC_MAX_FLOATS ((size_t)1 << 30)
+zb_status zb_grad_norm_static(const float* grads, size_t n, double* sq_out, int32_t* nonfinite_out,
+                              void* hip_stream);
+
 /* Copies between host fp32 buffers and stage tensors (converting to/from the stage's
  * data type).  bytes must equal 4 * number of elements.  Both wait for the device. */
 zb_status zb_get_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, void* host_dst, size_t bytes);

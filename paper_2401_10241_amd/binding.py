@@ -115,6 +115,7 @@ _sig = {
     "zb_stage_stash_bytes": [C.c_void_p, _P(C.c_double), _P(C.c_double)],
     "zb_profile_enable": [C.c_void_p, C.c_int32],
     "zb_profile_read": [C.c_void_p, _P(zb_kernel_stat), C.c_int32, _P(C.c_int32)],
+    "zb_grad_norm_static": [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p],
 }
 for _name, _args in _sig.items():
     _f = getattr(lib, _name)
@@ -249,6 +250,16 @@ def order_memory_peak(ops, m_b: float, m_w: float) -> float:
     if rc != OK:
         raise ZbError(rc, "zb_order_memory_peak")
     return peak.value
+
+
+GRAD_NORM_STATIC_MAX_FLOATS = 1 << 30
+
+
+def grad_norm_static(grads_ptr: int, n: int, sq_out_ptr: int, nonfinite_out_ptr: int, stream_handle: int = 0):
+    """zb_grad_norm_static: all three pointers are device addresses (ints), stream_handle a hipStream_t or 0."""
+    rc = lib.zb_grad_norm_static(grads_ptr, n, sq_out_ptr, nonfinite_out_ptr, stream_handle or None)
+    if rc != OK:
+        raise ZbError(rc, "zb_grad_norm_static")
 
 
 @dataclass

@@ -3,6 +3,9 @@
 // Every decision (step or not, gradient scale, rollback, redo) is taken by a one-thread kernel
 // that writes predicates into OptDevState; the heavy kernels read them and return at once when
 // switched off, so the host never waits between the steps of the protocol.
+#include <mutex>
+
+#include "../../include/zb_stage.h"
 #include "zb_common.h"
 
 namespace zb {
@@ -67,7 +70,7 @@ __global__ __launch_bounds__(256) void grad_sumsq_mid_kernel(const double* __res
 // one workgroup; partial sums are added in a fixed order
 __global__ __launch_bounds__(256) void grad_sumsq_final_kernel(const double* __restrict__ partial_sq,
                                                                const int* __restrict__ partial_nf, int blocks,
-                                                               OptDevState* st) {
+                                                               double* __restrict__ out_sq, int* __restrict__ out_nf) {
   __shared__ double red[256];
   __shared__ int redf[256];
   double acc = 0.0;
@@ -85,8 +88,8 @@ __global__ __launch_bounds__(256) void grad_sumsq_final_kernel(const double* __r
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    st->local_sq = red[0];
-    st->local_nonfinite = redf[0] ? 1 : 0;
+    *out_sq = red[0];
+    *out_nf = redf[0] ? 1 : 0;
   }
 }
 
@@ -258,8 +261,9 @@ size_t grad_sumsq_partials(size_t n) {
   return p1 + p2;
 }
 
-hipError_t launch_grad_sumsq(const float* g, size_t n, double* partial_sq, int* partial_nf, OptDevState* st,
-                             hipStream_t s) {
+// the three levels; the result goes to *out_sq / *out_nf (device)
+static hipError_t sumsq_levels(const float* g, size_t n, double* partial_sq, int* partial_nf, double* out_sq,
+                               int* out_nf, hipStream_t s) {
   if (n % 4 != 0 || n == 0) return hipErrorInvalidValue;
   const size_t n4 = n / 4;
   const size_t p1 = (n4 + 255) / 256, p2 = (p1 + kSumsqFan - 1) / kSumsqFan;
@@ -269,8 +273,12 @@ hipError_t launch_grad_sumsq(const float* g, size_t n, double* partial_sq, int* 
   if (e != hipSuccess) return e;
   grad_sumsq_mid_kernel<<<(unsigned)p2, 256, 0, s>>>(partial_sq, partial_nf, p1, partial_sq + p1, partial_nf + p1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  grad_sumsq_final_kernel<<<1, 256, 0, s>>>(partial_sq + p1, partial_nf + p1, (int)p2, st);
+  grad_sumsq_final_kernel<<<1, 256, 0, s>>>(partial_sq + p1, partial_nf + p1, (int)p2, out_sq, out_nf);
   return hipGetLastError();
+}
+hipError_t launch_grad_sumsq(const float* g, size_t n, double* partial_sq, int* partial_nf, OptDevState* st,
+                             hipStream_t s) {
+  return sumsq_levels(g, n, partial_sq, partial_nf, &st->local_sq, &st->local_nonfinite, s);
 }
 hipError_t launch_decide_optimistic(OptDevState* st, OptHyper hp, double prev_sq, int prev_nf, int force,
                                     hipStream_t s) {
@@ -332,3 +340,58 @@ hipError_t launch_adamw_rollback(float* theta, float* m, float* v, const float* 
 }
 
 }  // namespace zb
+
+// ---------------------------------------------------------------------------------------------------------
+// Squared gradient norm and non-finite flag for callers that cannot allocate: the partial sums of the three
+// reduction levels live in a file-scope device array instead of the stage's arena.
+// ---------------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kStaticMaxFloats = (size_t)1 << 30;  // == ZB_GRAD_NORM_STATIC_MAX_FLOATS
+constexpr size_t kStaticP1 = (kStaticMaxFloats / 4 + 255) / 256;
+constexpr size_t kStaticPartials = kStaticP1 + (kStaticP1 + zb::kSumsqFan - 1) / zb::kSumsqFan;
+constexpr size_t kStaticSqBytes = (kStaticPartials * sizeof(double) + 255) / 256 * 256;
+constexpr size_t kStaticBytes = kStaticSqBytes + kStaticPartials * sizeof(int);  // about 12.6 MB
+static_assert(kStaticMaxFloats == ZB_GRAD_NORM_STATIC_MAX_FLOATS, "header and kernel file disagree");
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// Every device holds its own copy of `scratch` at its own address: looked up once per device, with that
+// device current, and only this pointer (never the array's name) is handed to kernels.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+hipError_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" zb_status zb_grad_norm_static(const float* grads, size_t n, double* sq_out, int32_t* nonfinite_out,
+                                         void* hip_stream) {
+  if (!grads || !sq_out || !nonfinite_out) return ZB_EINVAL;
+  if (n == 0 || n % 4 != 0 || n > kStaticMaxFloats) return ZB_EINVAL;
+  if (reinterpret_cast<uintptr_t>(grads) & 15) return ZB_EINVAL;
+  void* base = nullptr;
+  if (scratch_of_current_device(&base) != hipSuccess) return ZB_EDEVICE;
+  double* partial_sq = reinterpret_cast<double*>(base);
+  int* partial_nf = reinterpret_cast<int*>(reinterpret_cast<unsigned char*>(base) + kStaticSqBytes);
+  // every partial the later levels read is written by the level before it in the same call: nothing has to
+  // start at zero, whatever the previous call left behind
+  const hipError_t e = zb::sumsq_levels(grads, n, partial_sq, partial_nf, sq_out, nonfinite_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ZB_OK : ZB_EDEVICE;
+}
