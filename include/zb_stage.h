@@ -186,9 +186,13 @@ typedef struct { double m_limit, m_b, m_w; } zb_memory_model;
 zb_status zb_simulate_pipeline(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times,
                                int32_t fused_backward, double* cost, double* bubble_rate, double* stage_span);
 
-/* Heuristic scheduler of Sec. 3.1 for one setting of its two binary options (one more warm-up forward
- * although it delays the first backward; no running ahead with forwards once a stage leads its successor
- * by one).  Writes all p stage orders to orders[p*3m] (host).  ZB_ENOMEM if m_limit admits no schedule. */
+/* Heuristic scheduler of Sec. 3.1 for one setting of its two binary options: extra_warmup_f = a stage that
+ * would idle before its first backward takes one more warm-up forward although that delays the backward;
+ * skip_f = a stage that leads its successor by more than one forward leaves a round's forward out when it has a
+ * W to run instead.  The steps run as the section lists them: warm-up forwards within the memory limit (stage
+ * i+1 at most one fewer than stage i), rounds of one B and one F per stage with W filling the gaps and
+ * releasing memory, the remaining W.  Writes all p stage orders to orders[p*3m] (host).  ZB_ENOMEM if
+ * m_limit admits no schedule. */
 zb_status zb_auto_schedule(int32_t p, int32_t m, const zb_pass_times* times, const zb_memory_model* mem,
                            int32_t extra_warmup_f, int32_t skip_f, zb_op* orders);
 

@@ -85,153 +85,131 @@ bool run_timing(int p, int m, const zb_op* orders, const Times& t, bool fused_ba
   return true;
 }
 
-// The heuristic of Sec. 3.1.  All stages share one clock; repeatedly every unfinished stage proposes
-// (pass, start time) from what has been decided so far, the proposal that starts first is carried out
-// (lowest stage on ties) and all stages propose again.
-class Heuristic {
+// The heuristic of Sec. 3.1, its four steps in the order the section gives them.
+//   Step 1 (warm-up): stage 0 may hold floor(M_limit / M_B) forwards, every later stage one fewer than the
+//   stage before it (step 3's guarantee that stage i stays a forward ahead of stage i+1), never fewer than
+//   one.  How many of those a stage takes depends on when its first backward can start, which depends on the
+//   stages after it, so the counts are settled from the last stage back to the first; the forwards of a stage
+//   run back to back from the moment the first microbatch reaches it.
+//   Step 2 (steady state): rounds of one backward per stage (last stage first) and one forward per stage
+//   (first stage first).  A pass that cannot start yet leaves a gap; pending W go into it while a whole one
+//   fits, and one more when idling instead would raise the largest cumulative bubble of all stages.  W also
+//   run to make room for a forward that does not fit under M_limit.
+//   Step 3: the forward of a round is left out if it would bring the stage level with its predecessor, or -
+//   second option - if the stage leads its successor by more than one and has a W to work on instead; the
+//   forward that the next round's backward needs is always taken.
+//   Step 4: the W that are left.
+struct StageClock {
+  double now = 0, mem = 0, bubble = 0;
+  int nf = 0, nb = 0, nw = 0, len = 0;
+};
+
+class RoundScheduler {
  public:
-  Heuristic(int p, int m, const Times& t, const zb_memory_model& mm, bool extra_warmup_f, bool skip_f)
-      : p_(p), m_(m), t_(t), mm_(mm), extra_(extra_warmup_f), skip_(skip_f) {
-    tol_ = 1e-9 * (t.f + t.b + t.w);
+  RoundScheduler(int p, int m, const Times& t, const zb_memory_model& mm, zb_op* out)
+      : p_(p), m_(m), t_(t), mm_(mm), out_(out), st_(p), endf_((size_t)p * m, 0.0), endb_((size_t)p * m, 0.0) {
+    eps_ = 1e-9 * (t.f + t.b + t.w);
     cap_ = mm.m_limit * (1 + 1e-12);
-    clock_.assign(p, 0.0);
-    nf_.assign(p, 0);
-    nb_.assign(p, 0);
-    nw_.assign(p, 0);
-    mem_.assign(p, 0.0);
-    idle_.assign(p, 0.0);
-    started_.assign(p, 0);
-    last_fb_.assign(p, ZB_PASS_F);
-    end_f_.assign((size_t)p * m, 0.0);
-    end_b_.assign((size_t)p * m, 0.0);
   }
 
-  // orders: [p][3m]; false if no stage can run a pass (memory limit too small)
-  bool run(zb_op* orders) {
-    std::vector<int> len(p_, 0);
-    const size_t n = (size_t)3 * m_;
-    for (size_t step = 0; step < (size_t)p_ * n; ++step) {
-      double max_idle = idle_[0];
-      for (int i = 1; i < p_; ++i)
-        if (idle_[i] > max_idle) max_idle = idle_[i];
-      int bi = -1, bpass = 0;
-      double bstart = 0;
-      for (int i = 0; i < p_; ++i) {
-        if (len[i] == (int)n) continue;
-        int pass;
-        double start;
-        if (!propose(i, max_idle, &pass, &start)) continue;
-        if (bi < 0 || start < bstart) { bi = i; bpass = pass; bstart = start; }
-      }
-      if (bi < 0) return false;
-      const int i = bi;
-      int k;
-      if (started_[i]) idle_[i] += bstart - clock_[i];
-      started_[i] = 1;
-      const double e = bstart + t_.of(bpass);
-      clock_[i] = e;
-      if (bpass == ZB_PASS_F) {
-        k = nf_[i]++;
-        end_f_[(size_t)i * m_ + k] = e;
-        last_fb_[i] = ZB_PASS_F;
-        mem_[i] += mm_.m_b;
-      } else if (bpass == ZB_PASS_B) {
-        k = nb_[i]++;
-        end_b_[(size_t)i * m_ + k] = e;
-        last_fb_[i] = ZB_PASS_B;
-        mem_[i] += mm_.m_w - mm_.m_b;
-      } else {
-        k = nw_[i]++;
-        mem_[i] += -mm_.m_w;
-      }
-      orders[(size_t)i * n + len[i]++] = zb_op{bpass, k};
+  void plan_warmup(bool extra, std::vector<int>* counts) const {
+    const double eps = 1e-9 * (t_.f + t_.b);
+    std::vector<int> room(p_);
+    long long fit = (long long)(cap_ / mm_.m_b);
+    if (fit > m_) fit = m_;
+    room[0] = fit < 1 ? 1 : (int)fit;
+    for (int i = 1; i < p_; ++i) room[i] = room[i - 1] > 2 ? room[i - 1] - 1 : 1;
+    counts->assign(p_, 1);
+    double b0_done = 0;
+    for (int i = p_ - 1; i >= 0; --i) {
+      const double lead_in = i * (t_.f + t_.comm);  // the first microbatch reaches the stage
+      const double b0_can = i == p_ - 1 ? lead_in + 1 * t_.f : b0_done + t_.comm;
+      int n = 1;
+      while (n < room[i] && lead_in + (n + 1) * t_.f <= b0_can + eps) ++n;
+      if (extra && n < room[i] && lead_in + n * t_.f < b0_can - eps) ++n;
+      (*counts)[i] = n;
+      const double f_done = lead_in + n * t_.f;
+      b0_done = (b0_can > f_done ? b0_can : f_done) + t_.b;
     }
+  }
+
+  bool build(bool extra, bool skip) {
+    std::vector<int> warm;
+    plan_warmup(extra, &warm);
+    for (int i = 0; i < p_; ++i)
+      for (int q = 0; q < warm[i]; ++q) place(i, ZB_PASS_F);
+    for (int round = 0; round < m_; ++round) {
+      for (int i = p_ - 1; i >= 0; --i) {
+        soak(i, can_start(i, ZB_PASS_B));
+        place(i, ZB_PASS_B);
+      }
+      for (int i = 0; i < p_; ++i) {
+        StageClock& s = st_[i];
+        if (s.nf == m_) continue;
+        const bool owed = s.nf <= round + 1;  // B of the next round reads this forward
+        if (!owed) {
+          if (i > 0 && st_[i - 1].nf < m_ && s.nf + 1 >= st_[i - 1].nf) continue;
+          if (skip && i < p_ - 1 && s.nf - st_[i + 1].nf > 1 && s.nw < s.nb) continue;
+        }
+        while (!(s.mem + mm_.m_b <= cap_)) {
+          if (!(s.nw < s.nb)) return false;
+          place(i, ZB_PASS_W);
+        }
+        soak(i, can_start(i, ZB_PASS_F));
+        place(i, ZB_PASS_F);
+      }
+    }
+    for (int i = 0; i < p_; ++i)
+      while (st_[i].nw < st_[i].nb) place(i, ZB_PASS_W);
     return true;
   }
 
  private:
-  // W now, or wait for the earlier of the next backward (s_b, if known) and the allowed forward (s_f)
-  bool fill(int i, double c, bool has_w, double max_idle, bool know_b, double s_b, bool allow_f, double s_f,
-            int* pass, double* start) const {
-    double nxt = know_b ? s_b : kInf;
-    const bool take_f = allow_f && s_f < nxt;
-    if (take_f) nxt = s_f;
-    if (has_w) {
-      const double gap = nxt - c;
-      if (gap >= t_.w - tol_ || idle_[i] + gap > max_idle + tol_) {
-        *pass = ZB_PASS_W;
-        *start = c;
-        return true;
-      }
+  double can_start(int i, int pass) const {
+    const StageClock& s = st_[i];
+    double t = s.now;
+    if (pass == ZB_PASS_F && i > 0) {
+      const double a = endf_[(size_t)(i - 1) * m_ + s.nf] + t_.comm;
+      if (a > t) t = a;
+    } else if (pass == ZB_PASS_B && i < p_ - 1) {
+      const double a = endb_[(size_t)(i + 1) * m_ + s.nb] + t_.comm;
+      if (a > t) t = a;
     }
-    if (nxt < kInf) {
-      *pass = take_f ? ZB_PASS_F : ZB_PASS_B;
-      *start = nxt;
-      return true;
-    }
-    return false;
+    return t;
   }
 
-  bool propose(int i, double max_idle, int* pass, double* start) const {
-    const double c = clock_[i];
-    bool know_f = false, know_b = false;
-    double s_f = 0, s_b = 0;
-    if (nf_[i] < m_ && (i == 0 || nf_[i - 1] > nf_[i])) {
-      know_f = true;
-      s_f = c;
-      if (i > 0) {
-        const double a = end_f_[(size_t)(i - 1) * m_ + nf_[i]] + t_.comm;
-        if (a > s_f) s_f = a;
-      }
+  void place(int i, int pass) {
+    StageClock& s = st_[i];
+    const double at = can_start(i, pass);
+    if (s.len > 0) s.bubble += at - s.now;
+    s.now = at + t_.of(pass);
+    int k;
+    if (pass == ZB_PASS_F) { k = s.nf++; endf_[(size_t)i * m_ + k] = s.now; s.mem += mm_.m_b; }
+    else if (pass == ZB_PASS_B) { k = s.nb++; endb_[(size_t)i * m_ + k] = s.now; s.mem += mm_.m_w - mm_.m_b; }
+    else { k = s.nw++; s.mem += -mm_.m_w; }
+    out_[(size_t)i * 3 * m_ + s.len++] = zb_op{pass, k};
+  }
+
+  // pending W into the gap before a pass that can start at `until`
+  void soak(int i, double until) {
+    StageClock& s = st_[i];
+    while (s.nw < s.nb && s.now + t_.w <= until + eps_) place(i, ZB_PASS_W);
+    const double gap = until - s.now;
+    if (s.nw < s.nb && gap > eps_) {
+      double worst = st_[0].bubble;
+      for (int j = 1; j < p_; ++j)
+        if (st_[j].bubble > worst) worst = st_[j].bubble;
+      if (s.bubble + gap > worst + eps_) place(i, ZB_PASS_W);
     }
-    if (nb_[i] < nf_[i] && (i == p_ - 1 || nb_[i + 1] > nb_[i])) {
-      know_b = true;
-      s_b = c;
-      if (i < p_ - 1) {
-        const double a = end_b_[(size_t)(i + 1) * m_ + nb_[i]] + t_.comm;
-        if (a > s_b) s_b = a;
-      }
-    }
-    const bool has_w = nw_[i] < nb_[i];
-    const bool mem_ok = mem_[i] + mm_.m_b <= cap_;
-    const bool f_arrived = know_f && s_f <= c + tol_;
-    const bool b_now = know_b && s_b <= c + tol_;
-    const bool fits = know_f && (!know_b || s_f + t_.f <= s_b + tol_);
-    auto now = [&](int what) {
-      *pass = what;
-      *start = c;
-      return true;
-    };
-    if (nb_[i] == 0) {  // warm-up
-      if (b_now) return now(ZB_PASS_B);
-      const bool ok = know_f && mem_ok && (fits || (extra_ && (!know_b || s_f < s_b - tol_)));
-      return fill(i, c, has_w, max_idle, know_b, s_b, ok, s_f, pass, start);
-    }
-    if (nf_[i] == m_ && nb_[i] == m_) return has_w ? now(ZB_PASS_W) : false;
-    if (last_fb_[i] == ZB_PASS_B && nf_[i] < m_) {  // a forward is due
-      if (f_arrived) {
-        if (mem_ok) return now(ZB_PASS_F);
-        if (has_w) return now(ZB_PASS_W);  // release memory for the forward
-        if (b_now) return now(ZB_PASS_B);
-        return fill(i, c, has_w, max_idle, know_b, s_b, false, 0, pass, start);
-      }
-      if (b_now) return now(ZB_PASS_B);
-      return fill(i, c, has_w, max_idle, know_b, s_b, know_f && mem_ok, s_f, pass, start);
-    }
-    if (b_now) return now(ZB_PASS_B);  // a backward is due
-    const int lead = nf_[i] - (i < p_ - 1 ? nf_[i + 1] : nb_[i]);
-    const bool ok = know_f && mem_ok && fits && !(skip_ && lead >= 1);
-    return fill(i, c, has_w, max_idle, know_b, s_b, ok, s_f, pass, start);
   }
 
   int p_, m_;
   Times t_;
   zb_memory_model mm_;
-  bool extra_, skip_;
-  double tol_, cap_;
-  std::vector<double> clock_, mem_, idle_, end_f_, end_b_;
-  std::vector<int> nf_, nb_, nw_, last_fb_;
-  std::vector<char> started_;
+  zb_op* out_;
+  double eps_, cap_;
+  std::vector<StageClock> st_;
+  std::vector<double> endf_, endb_;
 };
 
 bool valid_memory(const zb_memory_model* mm) {
@@ -268,8 +246,8 @@ zb_status zb_auto_schedule(int32_t p, int32_t m, const zb_pass_times* times, con
                            int32_t extra_warmup_f, int32_t skip_f, zb_op* orders) {
   if (p < 1 || m < 1 || !orders || !valid_times(times) || !valid_memory(mem)) return ZB_EINVAL;
   const Times t{times->t_f, times->t_b, times->t_w, times->t_comm};
-  Heuristic h(p, m, t, *mem, extra_warmup_f != 0, skip_f != 0);
-  return h.run(orders) ? ZB_OK : ZB_ENOMEM;
+  RoundScheduler h(p, m, t, *mem, orders);
+  return h.build(extra_warmup_f != 0, skip_f != 0) ? ZB_OK : ZB_ENOMEM;
 }
 
 zb_status zb_auto_schedule_search(int32_t p, int32_t m, const zb_pass_times* times, const zb_memory_model* mem,
@@ -283,8 +261,8 @@ zb_status zb_auto_schedule_search(int32_t p, int32_t m, const zb_pass_times* tim
   double best = 0;
   for (int combo = 0; combo < 4; ++combo) {  // (0,0) (0,1) (1,0) (1,1); the first of equal costs wins
     const bool ew = (combo >> 1) != 0, sk = (combo & 1) != 0;
-    Heuristic h(p, m, t, *mem, ew, sk);
-    if (!h.run(trial.data())) continue;
+    RoundScheduler h(p, m, t, *mem, trial.data());
+    if (!h.build(ew, sk)) continue;
     std::vector<double> first, last;
     if (!run_timing(p, m, trial.data(), t, false, &first, &last)) continue;
     const double c = span_cost(first, last);
