@@ -115,6 +115,10 @@ def main():
                          "passes, 1F1B with the traditional single backward (B and W fused layer by layer), or ZB-V "
                          "(Sec. 6: the stage's layers as two chunks, 2m virtual microbatches; needs an even "
                          "number of layers)")
+    ap.add_argument("--w-group", type=int, default=1,
+                    help="hold the order's W passes back until this many can run side by side (zb_order_group_w: "
+                         "same results bit for bit, group-1 more microbatches of W stash); 1 = the order as the "
+                         "paper gives it (default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -144,8 +148,12 @@ def main():
             sys.exit(2)
         v_ops = zb.schedule_order_v(w.p, m)[w.stage]
         pb, pw, fl = zb.order_stash_need(v_ops)
+    elif args.w_group > 1:
+        v_ops = zb.order_group_w(zb.schedule_order(w.p, w.stage, m, kind), args.w_group)
+        pb, pw, fl = zb.order_stash_need(v_ops)
     else:
         pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, kind)
+    explicit = zbv or args.w_group > 1
     m_run = 2 * m if zbv else m          # virtual microbatches (chunk * m + microbatch) under ZB-V
     st = zb.Stage(fuse_bw=(args.order == "1F1B-fused"), chunks=(2 if zbv else 1), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
                   dtype=w.dtype, max_microbatches=m_run, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
@@ -164,7 +172,7 @@ def main():
         it = it_counter[0]
         it_counter[0] += 1
         st.begin_iteration(it, m_run)
-        if zbv:
+        if explicit:
             st.run_order(v_ops)
         else:
             st.run_schedule(w.p, w.stage, m, kind)
@@ -200,7 +208,8 @@ def main():
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "config": {"workload": f"{w.name}: stage {w.stage} of p={w.p}, "
                                + (f"ZB-{w.kind}" if args.order == "workload" else args.order)
-                               + f" order, m={m}, {w.layers} GPT "
+                               + (f" order with W held back into groups of {args.w_group}" if args.w_group > 1
+                                  else " order") + f", m={m}, {w.layers} GPT "
                                f"decoder layers h={w.hidden} a={w.heads} ffn={w.ffn} seq={w.seq} b={w.mb_size}"
                                + (", validated AdamW step" if w.optimizer else ""),
                    "model_flops_per_step": flops, "setup_seconds": round(setup_s, 1)},

@@ -217,6 +217,14 @@ zb_status zb_schedule_order_v(int32_t p, int32_t m, zb_op* orders);
 zb_status zb_simulate_pipeline_v(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times, double* cost,
                                  double* bubble_rate, double* stage_span);
 
+/* The same stage order with its W passes held back until `group` of them can run side by side (Sec. 2: a W
+ * may run anywhere after its B; Appendix A regroups deferred W the same way): every F and B keeps its place,
+ * a W moves behind later F / B passes until group W are waiting, the last ones run at the end.  W stay in
+ * their original sequence, so accumulated gradients keep every bit (see zb_backward_weight_group); the price
+ * is group - 1 more microbatches of W stash (zb_order_stash_need / zb_order_memory_peak on the result) and
+ * whatever the p-stage timing model says about the bubbles.  ops and out: n entries each (host), group >= 1. */
+zb_status zb_order_group_w(const zb_op* ops, int32_t n, int32_t group, zb_op* out);
+
 /* Peak of Appendix G's memory walk over one stage order of n entries. */
 zb_status zb_order_memory_peak(const zb_op* ops, int32_t n, double m_b, double m_w, double* peak);
 
@@ -276,6 +284,20 @@ zb_status zb_grad_norm_static(const float* grads, size_t n, double* sq_out, int3
  * data type).  bytes must equal 4 * number of elements.  Both wait for the device. */
 zb_status zb_get_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, void* host_dst, size_t bytes);
 zb_status zb_set_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, const void* host_src, size_t bytes);
+
+/* What B keeps for W (Table 1: the inputs and the output gradients of the four linears of a layer), as a
+ * debug read-out: columns cols[0..ncols) (host) of one such [tokens, width] matrix of microbatch mb, converted
+ * to fp32, into host_dst as a dense [tokens, ncols] matrix.  Valid between B(mb) and W(mb) (ZB_EORDER
+ * otherwise).  Widths: hidden, except FC2's input and FC1's output gradient (ffn) and the QKV projection's
+ * output gradient (3 hidden).  The weight gradient of a linear is the sum over microbatches of
+ * input^T * output-gradient, so an accumulated gradient entry can be recomputed from these.  Waits for the
+ * device. */
+enum {
+  ZB_S_QKV_IN = 0, ZB_S_PROJ_IN = 1, ZB_S_FC1_IN = 2, ZB_S_FC2_IN = 3,         /* A, C, U, G of the forward */
+  ZB_S_QKV_DOUT = 4, ZB_S_PROJ_DOUT = 5, ZB_S_FC1_DOUT = 6, ZB_S_FC2_DOUT = 7  /* their output gradients */
+};
+zb_status zb_get_stash_columns(zb_stage* st, int32_t which, int32_t layer, int32_t mb, const int32_t* cols,
+                               int32_t ncols, float* host_dst);
 
 /* Overwrites one element of INPUT_X / INPUT_DY of microbatch mb (e.g. with NaN). */
 zb_status zb_inject(zb_stage* st, int32_t what, int32_t mb, int64_t elem, float value);

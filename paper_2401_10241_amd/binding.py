@@ -35,6 +35,7 @@ PARAM_INDEX = {n: i for i, n in enumerate(
 T_PARAM, T_GRAD, T_ADAM_M, T_ADAM_V = 0, 16, 32, 48
 T_INPUT_X, T_INPUT_DY, T_OUTPUT_Y, T_OUTPUT_DX = 64, 65, 66, 67
 T_FLAT_PARAMS, T_FLAT_GRADS, T_FLAT_ADAM_M, T_FLAT_ADAM_V = 80, 81, 82, 83
+S_QKV_IN, S_PROJ_IN, S_FC1_IN, S_FC2_IN, S_QKV_DOUT, S_PROJ_DOUT, S_FC1_DOUT, S_FC2_DOUT = range(8)
 OUTCOME_NAMES = ("COMMITTED", "SKIPPED_LOCAL", "ROLLED_BACK_NONFINITE", "ROLLED_BACK_RECLIPPED",
                  "DEFERRED_CLIPPED", "DEFERRED_SKIPPED")
 
@@ -103,6 +104,7 @@ _sig = {
     "zb_auto_schedule_search": [C.c_int32, C.c_int32, _P(zb_pass_times), _P(zb_memory_model), _P(zb_op),
                                 _P(C.c_double), _P(C.c_double), _P(C.c_int32), _P(C.c_int32)],
     "zb_order_memory_peak": [_P(zb_op), C.c_int32, C.c_double, C.c_double, _P(C.c_double)],
+    "zb_order_group_w": [_P(zb_op), C.c_int32, C.c_int32, _P(zb_op)],
     "zb_schedule_order_v": [C.c_int32, C.c_int32, _P(zb_op)],
     "zb_simulate_pipeline_v": [C.c_int32, C.c_int32, _P(zb_op), _P(zb_pass_times), _P(C.c_double), _P(C.c_double),
                                _P(C.c_double)],
@@ -110,6 +112,7 @@ _sig = {
     "zb_get_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
     "zb_set_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t],
     "zb_inject": [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_float],
+    "zb_get_stash_columns": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _P(C.c_int32), C.c_int32, C.c_void_p],
     "zb_synchronize": [C.c_void_p],
     "zb_stage_model_flops": [C.c_void_p, C.c_int32, _P(C.c_double)],
     "zb_stage_stash_bytes": [C.c_void_p, _P(C.c_double), _P(C.c_double)],
@@ -241,6 +244,15 @@ def simulate_pipeline_v(orders, m: int, t_f: float, t_b: float, t_w: float,
     if rc != OK:
         raise ZbError(rc, "zb_simulate_pipeline_v")
     return cost.value, rate.value, list(spans)
+
+
+def order_group_w(ops, group: int) -> List[Tuple[int, int]]:
+    """zb_order_group_w: the order with its W passes held back into groups of `group`."""
+    out = (zb_op * max(len(ops), 1))()
+    rc = lib.zb_order_group_w(_pack_order(ops), len(ops), group, out)
+    if rc != OK:
+        raise ZbError(rc, "zb_order_group_w")
+    return [(out[i].pass_, out[i].mb) for i in range(len(ops))]
 
 
 def order_memory_peak(ops, m_b: float, m_w: float) -> float:
@@ -403,6 +415,13 @@ class Stage:
     def set_tensor(self, what: int, layer: int, mb: int, value: np.ndarray):
         v = np.ascontiguousarray(value, np.float32)
         self._call(lib.zb_set_tensor, what, layer, mb, v.ctypes.data_as(C.c_void_p), v.nbytes)
+
+    def get_stash_columns(self, which: int, layer: int, mb: int, cols) -> np.ndarray:
+        """zb_get_stash_columns: [tokens, len(cols)] fp32."""
+        idx = (C.c_int32 * len(cols))(*[int(c) for c in cols])
+        out = np.empty((self.tokens, len(cols)), np.float32)
+        self._call(lib.zb_get_stash_columns, which, layer, mb, idx, len(cols), out.ctypes.data_as(C.c_void_p))
+        return out
 
     def inject(self, what: int, mb: int, elem: int, value: float):
         self._call(lib.zb_inject, what, mb, elem, value)

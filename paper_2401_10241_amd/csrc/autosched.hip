@@ -414,6 +414,23 @@ zb_status zb_simulate_pipeline_v(int32_t p, int32_t m, const zb_op* orders, cons
   return ZB_OK;
 }
 
+zb_status zb_order_group_w(const zb_op* ops, int32_t n, int32_t group, zb_op* out) {
+  if (!ops || !out || n < 0 || group < 1) return ZB_EINVAL;
+  std::vector<zb_op> held;
+  int32_t q = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (ops[i].pass < 0 || ops[i].pass > 2) return ZB_EINVAL;
+    if (ops[i].pass != ZB_PASS_W) { out[q++] = ops[i]; continue; }
+    held.push_back(ops[i]);
+    if ((int32_t)held.size() == group) {
+      for (const zb_op& w : held) out[q++] = w;
+      held.clear();
+    }
+  }
+  for (const zb_op& w : held) out[q++] = w;
+  return ZB_OK;
+}
+
 zb_status zb_order_memory_peak(const zb_op* ops, int32_t n, double m_b, double m_w, double* peak) {
   if (!ops || n < 0 || !peak) return ZB_EINVAL;
   double cur = 0, top = 0;

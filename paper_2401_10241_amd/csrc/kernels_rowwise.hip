@@ -482,6 +482,23 @@ template <typename T> hipError_t launch_convert_to_f32(const T* src, float* dst,
   convert_to_f32_kernel<T><<<grid_for(n), 256, 0, s>>>(src, dst, n);
   return hipGetLastError();
 }
+// dst[r, c] = (float) src[r * ld + cols[c]]: a few columns of a row-major matrix, for the debug getter
+template <typename T>
+__global__ void gather_columns_kernel(const T* __restrict__ src, long ld, int rows, const int* __restrict__ cols,
+                                      int ncols, float* __restrict__ dst) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows * ncols) return;
+  const size_t r = i / ncols;
+  const int c = (int)(i - r * ncols);
+  dst[i] = to_f32(src[r * ld + cols[c]]);
+}
+template <typename T>
+hipError_t launch_gather_columns(const T* src, long ld, int rows, const int* cols, int ncols, float* dst,
+                                 hipStream_t s) {
+  if (rows <= 0 || ncols <= 0) return hipErrorInvalidValue;
+  gather_columns_kernel<T><<<grid_for((size_t)rows * ncols), 256, 0, s>>>(src, ld, rows, cols, ncols, dst);
+  return hipGetLastError();
+}
 template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStream_t s) {
   poke_kernel<T><<<1, 1, 0, s>>>(dst, idx, v);
   return hipGetLastError();
@@ -496,6 +513,7 @@ template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStr
                                                    int, hipStream_t);                                           \
   template hipError_t launch_convert_from_f32<T>(const float*, T*, size_t, hipStream_t);                         \
   template hipError_t launch_convert_to_f32<T>(const T*, float*, size_t, hipStream_t);                           \
+  template hipError_t launch_gather_columns<T>(const T*, long, int, const int*, int, float*, hipStream_t);        \
   template hipError_t launch_poke<T>(T*, size_t, float, hipStream_t);
 ZB_INST(float)
 ZB_INST(bf16_t)

@@ -1016,6 +1016,50 @@ zb_status zb_set_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, c
   return ZB_OK;
 }
 
+zb_status zb_get_stash_columns(zb_stage* st, int32_t which, int32_t layer, int32_t mb, const int32_t* cols,
+                               int32_t ncols, float* host_dst) {
+  if (!st || !cols || !host_dst) return ZB_EINVAL;
+  st->err.clear();
+  if (which < ZB_S_QKV_IN || which > ZB_S_FC2_DOUT) return fail(st, ZB_EINVAL, "unknown stash selector");
+  if (layer < 0 || layer >= st->L) return fail(st, ZB_EINVAL, "layer out of range");
+  if (st->m <= 0 || mb < 0 || mb >= st->m) return fail(st, ZB_EINVAL, "microbatch out of range");
+  if (!st->done[ZB_PASS_B][mb] || st->done[ZB_PASS_W][mb])
+    return fail(st, ZB_EORDER, "the W stash of a microbatch exists between its B and its W");
+  int lo_l, hi_l;
+  layer_range(st, mb, &lo_l, &hi_l);
+  if (layer < lo_l || layer > hi_l) return fail(st, ZB_EINVAL, "the microbatch does not run through this layer");
+  const int h = st->h, f = st->ffn;
+  const LayerOff& q = st->lo[layer];
+  const char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mb];
+  const char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
+  const char* src = nullptr;
+  int width = h;
+  switch (which) {
+    case ZB_S_QKV_IN: src = fw + q.fw_a; break;
+    case ZB_S_PROJ_IN: src = fw + q.fw_c; break;
+    case ZB_S_FC1_IN: src = fw + q.fw_u; break;
+    case ZB_S_FC2_IN: src = fw + q.fw_g; width = f; break;
+    case ZB_S_QKV_DOUT: src = bw + q.bw_dqkv; width = 3 * h; break;
+    case ZB_S_PROJ_DOUT: src = bw + q.bw_dy1; break;
+    case ZB_S_FC1_DOUT: src = bw + q.bw_dfh; width = f; break;
+    default:  // the top layer's FC2 output gradient is the upstream gradient itself
+      src = layer == hi_l ? st->in_dy + st->act_bytes * (size_t)mb : bw + q.bw_dy;
+      break;
+  }
+  if (ncols < 1 || (size_t)ncols * ((size_t)st->T + 1) > st->staging_floats)
+    return fail(st, ZB_EINVAL, "ncols must be positive and tokens * ncols + ncols floats must fit the staging buffer");
+  for (int c = 0; c < ncols; ++c)
+    if (cols[c] < 0 || cols[c] >= width) return fail(st, ZB_EINVAL, "column index out of range");
+  hipStream_t s = st->stream;
+  int* dcols = reinterpret_cast<int*>(st->staging + (size_t)st->T * ncols);
+  ZB_HIP(st, hipMemcpyAsync(dcols, cols, sizeof(int32_t) * (size_t)ncols, hipMemcpyHostToDevice, s));
+  if (st->bf16) ZB_HIP(st, launch_gather_columns<bf16_t>((const bf16_t*)src, width, st->T, dcols, ncols, st->staging, s));
+  else ZB_HIP(st, launch_gather_columns<float>((const float*)src, width, st->T, dcols, ncols, st->staging, s));
+  ZB_HIP(st, hipMemcpyAsync(host_dst, st->staging, sizeof(float) * (size_t)st->T * ncols, hipMemcpyDeviceToHost, s));
+  ZB_HIP(st, hipStreamSynchronize(s));
+  return ZB_OK;
+}
+
 zb_status zb_inject(zb_stage* st, int32_t what, int32_t mb, int64_t elem, float value) {
   if (!st) return ZB_EINVAL;
   st->err.clear();

@@ -148,6 +148,10 @@ hipError_t launch_transpose_bf16(const bf16_t* src, bf16_t* dst, int rows, int c
 template <typename T> hipError_t launch_convert_from_f32(const float* src, T* dst, size_t n, hipStream_t s);
 template <typename T> hipError_t launch_convert_to_f32(const T* src, float* dst, size_t n, hipStream_t s);
 template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStream_t s);
+// dst[r, c] (fp32, dense [rows, ncols]) = src[r * ld + cols[c]]; cols is a device array
+template <typename T>
+hipError_t launch_gather_columns(const T* src, long ld, int rows, const int* cols, int ncols, float* dst,
+                                 hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // optimizer (Sec. 4 and Appendix C).  All decisions live in OptDevState on the device.

@@ -79,3 +79,30 @@ def test_stage_refuses_to_run_without_a_gpu():
     with pytest.raises(RuntimeError):
         zb.Stage(layers=1, hidden=64, heads=1, ffn=256, seq=16, max_microbatches=1, max_pending_b=1,
                  max_pending_w=1, max_inflight=1)
+
+
+def test_order_group_w_keeps_every_pass_and_the_w_sequence():
+    import paper_2401_10241_amd as zb
+    from oracle.schedule import check_order, stash_profile
+    for kind in ("1F1B", "H1", "H2"):
+        for p, sigma, m in ((4, 1, 8), (16, 8, 48), (8, 7, 5), (3, 0, 2)):
+            base = zb.schedule_order(p, sigma, m, kind)
+            assert zb.order_group_w(base, 1) == base
+            for group in (2, 3, 4, 64):
+                got = zb.order_group_w(base, group)
+                check_order(got, m)                                      # F_k before B_k before W_k, each once
+                assert [op for op in got if op[0] != 2] == [op for op in base if op[0] != 2]   # F and B keep their places
+                assert [k for c, k in got if c == 2] == [k for c, k in base if c == 2]         # W in their sequence
+                runs, cur = [], 0
+                for c, _ in got:                                          # lengths of the runs of consecutive W
+                    if c == 2:
+                        cur += 1
+                    elif cur:
+                        runs.append(cur)
+                        cur = 0
+                assert all(r >= min(group, m) for r in runs)             # only the last run (at the end) may be shorter
+                _, _, _, _, max_w = stash_profile(got)
+                _, _, _, _, base_w = stash_profile(base)
+                assert max_w <= base_w + group - 1 or max_w <= m
+    buf = (zb.binding.zb_op * 4)()
+    assert zb.lib.zb_order_group_w(buf, 3, 0, buf) == zb.EINVAL
