@@ -76,12 +76,12 @@ class StageOracle:
             self.work.append(Wk)
 
     def _flat(self, dicts) -> np.ndarray:
-        return np.concatenate([d[k].reshape(-1) for d in dicts for k in PARAM_ORDER])
+        return np.concatenate([d[k].reshape(-1) for d in dicts for k in d])
 
     def _unflat(self, vec, dicts):
         o = 0
         for d in dicts:
-            for k in PARAM_ORDER:
+            for k in d:
                 n = d[k].size
                 d[k][...] = vec[o:o + n].reshape(d[k].shape)
                 o += n
@@ -96,7 +96,7 @@ class StageOracle:
         self._bstash: Dict[int, list] = {}
         self._wstash: Dict[int, list] = {}
         self._done = {PASS_F: set(), PASS_B: set(), PASS_W: set()}
-        self.grads = [{k: np.zeros_like(P[k]) for k in PARAM_ORDER} for P in self.master]
+        self.grads = [{k: np.zeros_like(v) for k, v in P.items()} for P in self.master]
         self.max_pending_b = self.max_pending_w = 0
 
     def set_input(self, mb: int, X: np.ndarray):

@@ -33,11 +33,11 @@ import numpy as np
 __all__ = [
     "Workload", "WORKLOADS", "workload", "PARAM_NAMES", "param_shape",
     "stage_params", "stage_input", "upstream_grad", "rest_state",
-    "round_to_bf16", "nan_injection",
+    "round_to_bf16", "nan_injection", "end_stage_params", "token_ids", "target_ids",
 ]
 
 # tensor kinds used in stream ids
-_K_PARAM, _K_X, _K_DY, _K_REST, _K_INJECT = 1, 2, 3, 4, 5
+_K_PARAM, _K_X, _K_DY, _K_REST, _K_INJECT, _K_IDS, _K_TARGETS, _K_END = 1, 2, 3, 4, 5, 6, 7, 8
 
 #: per-layer parameter names in the order used everywhere (weights are [in, out])
 PARAM_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo",
@@ -183,3 +183,41 @@ def rest_state(w: Workload, it: int, scale: float = 1.0) -> float:
     """Seeded squared gradient norm contributed by the stages after this one."""
     gen = np.random.Generator(np.random.Philox(key=np.array([w.seed, _stream_id(_K_REST, 0, it, 0)], dtype=np.uint64)))
     return float(scale * (0.5 + gen.random()))
+
+
+# ---------------------------------------------------------------------------------------------
+# first / last stage (Sec. 5.1 of the paper: embedding lookup in the first, loss in the last)
+# ---------------------------------------------------------------------------------------------
+def end_stage_params(w: Workload, role: str, vocab: int) -> Dict[str, np.ndarray]:
+    """Stage-level fp32 parameters: role "first" -> token and position tables N(0, 0.02^2);
+    role "last" -> final LayerNorm (gamma 1, beta 0) and the head matrix [hidden, vocab] N(0, 0.02^2)."""
+    h = w.hidden
+    if role == "first":
+        return {"emb_tok": _normal(w.seed, _stream_id(_K_END, 0, 0, 0, 0), (vocab, h), 0.02),
+                "emb_pos": _normal(w.seed, _stream_id(_K_END, 0, 0, 0, 1), (w.seq, h), 0.02)}
+    if role == "last":
+        return {"lnf_g": np.ones((h,), np.float32), "lnf_b": np.zeros((h,), np.float32),
+                "w_head": _normal(w.seed, _stream_id(_K_END, 0, 0, 0, 2), (h, vocab), 0.02)}
+    raise ValueError("role must be 'first' or 'last'")
+
+
+def _zipf_ids(seed: int, sid: int, n: int, vocab: int) -> np.ndarray:
+    """Token ids with the rank-frequency shape of text: P(rank r) proportional to 1 / (r + 2.7), ranks mapped
+    to ids by a fixed seeded permutation (so frequent ids are spread over the table).  A microbatch of 1024
+    tokens then repeats its frequent ids many times, which is what the embedding gradient has to cope with."""
+    gen = np.random.Generator(np.random.Philox(key=np.array([seed, sid], dtype=np.uint64)))
+    weights = 1.0 / (np.arange(vocab, dtype=np.float64) + 2.7)
+    cdf = np.cumsum(weights)
+    ranks = np.searchsorted(cdf, gen.random(n) * cdf[-1], side="right")
+    perm = np.random.Generator(np.random.Philox(key=np.array([seed, 0x5EED], dtype=np.uint64))).permutation(vocab)
+    return perm[np.minimum(ranks, vocab - 1)].astype(np.int32)
+
+
+def token_ids(w: Workload, it: int, mb: int, vocab: int) -> np.ndarray:
+    """int32 [tokens] input ids of microbatch mb (first stage)."""
+    return _zipf_ids(w.seed, _stream_id(_K_IDS, 0, it, mb), w.tokens, vocab)
+
+
+def target_ids(w: Workload, it: int, mb: int, vocab: int) -> np.ndarray:
+    """int32 [tokens] target ids of microbatch mb (last stage)."""
+    return _zipf_ids(w.seed, _stream_id(_K_TARGETS, 0, it, mb), w.tokens, vocab)
