@@ -119,6 +119,10 @@ def main():
                     help="hold the order's W passes back until this many can run side by side (zb_order_group_w: "
                          "same results bit for bit, group-1 more microbatches of W stash); 1 = the order as the "
                          "paper gives it (default)")
+    ap.add_argument("--role", default="middle", choices=["middle", "first", "last"],
+                    help="first / last stage of the pipeline (Sec. 5.1): one transformer layer fewer than the "
+                         "workload's middle stage, plus the embedding lookup (first) or the final LayerNorm, head "
+                         "and cross-entropy loss (last), vocabulary 50432; order of stage 0 / stage p-1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -138,6 +142,13 @@ def main():
     w = zb_inputs.workload(args.workload)
     if args.m:
         w = w.scaled(m=args.m)
+    vocab = 0
+    if args.role != "middle":
+        if w.layers < 2 or args.order == "ZB-V":
+            print("bench.py: --role first/last needs a workload with at least two layers and one chunk", file=sys.stderr)
+            sys.exit(2)
+        vocab = 50432   # a GPT-3-like vocabulary (50257 entries) padded to a multiple of 256
+        w = w.scaled(layers=w.layers - 1, stage=0 if args.role == "first" else w.p - 1)
     m = w.m
     torch.cuda.set_device(0)
     kind = w.kind if args.order == "workload" else "1F1B"
@@ -155,15 +166,23 @@ def main():
         pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, kind)
     explicit = zbv or args.w_group > 1
     m_run = 2 * m if zbv else m          # virtual microbatches (chunk * m + microbatch) under ZB-V
-    st = zb.Stage(fuse_bw=(args.order == "1F1B-fused"), chunks=(2 if zbv else 1), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+    st = zb.Stage(role=args.role, vocab=vocab, fuse_bw=(args.order == "1F1B-fused"), chunks=(2 if zbv else 1), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
                   dtype=w.dtype, max_microbatches=m_run, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
                   lr=w.lr, beta1=w.beta1, beta2=w.beta2, adam_eps=w.adam_eps, weight_decay=w.weight_decay,
                   clip=w.clip, ln_eps=w.ln_eps)
     t0 = time.perf_counter()
     st.set_params(zb_inputs.stage_params(w))
+    if args.role != "middle":
+        st.set_stage_params(zb_inputs.end_stage_params(w, args.role, vocab))
     for k in range(m_run):
-        st.set_tensor(zb.T_INPUT_X, 0, k, zb_inputs.stage_input(w, 0, k))
-        st.set_tensor(zb.T_INPUT_DY, 0, k, zb_inputs.upstream_grad(w, 0, k))
+        if args.role == "first":
+            st.set_ids(zb.T_INPUT_IDS, k, zb_inputs.token_ids(w, 0, k, vocab))
+        else:
+            st.set_tensor(zb.T_INPUT_X, 0, k, zb_inputs.stage_input(w, 0, k))
+        if args.role == "last":
+            st.set_ids(zb.T_TARGET_IDS, k, zb_inputs.target_ids(w, 0, k, vocab))
+        else:
+            st.set_tensor(zb.T_INPUT_DY, 0, k, zb_inputs.upstream_grad(w, 0, k))
     setup_s = time.perf_counter() - t0
 
     it_counter = [0]
@@ -206,7 +225,7 @@ def main():
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
-        "config": {"workload": f"{w.name}: stage {w.stage} of p={w.p}, "
+        "config": {"workload": f"{w.name}: " + (f"{args.role} " if args.role != "middle" else "") + f"stage {w.stage} of p={w.p}, "
                                + (f"ZB-{w.kind}" if args.order == "workload" else args.order)
                                + (f" order with W held back into groups of {args.w_group}" if args.w_group > 1
                                   else " order") + f", m={m}, {w.layers} GPT "
@@ -261,7 +280,7 @@ def main():
     del st
     torch.cuda.empty_cache()
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.role == "middle":
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
 

@@ -55,6 +55,9 @@ typedef enum {
 typedef enum { ZB_FP32 = 0, ZB_BF16 = 1 } zb_dtype;
 typedef enum { ZB_1F1B = 0, ZB_H1 = 1, ZB_H2 = 2 } zb_kind;
 typedef enum { ZB_PASS_F = 0, ZB_PASS_B = 1, ZB_PASS_W = 2 } zb_pass;
+/* Sec. 5.1: the first stage of the pipeline also does the embedding lookup, the last one the loss
+ * computation (each holds one transformer layer fewer to make up for it: pass that count as `layers`). */
+typedef enum { ZB_ROLE_MIDDLE = 0, ZB_ROLE_FIRST = 1, ZB_ROLE_LAST = 2 } zb_role;
 typedef struct { int32_t pass, mb; } zb_op;
 
 /* Per-layer parameters, in the order used by every "param index" below. */
@@ -62,6 +65,11 @@ enum {
   ZB_P_LN1_G = 0, ZB_P_LN1_B, ZB_P_WQKV, ZB_P_BQKV, ZB_P_WO, ZB_P_BO,
   ZB_P_LN2_G, ZB_P_LN2_B, ZB_P_W1, ZB_P_B1, ZB_P_W2, ZB_P_B2, ZB_P_COUNT
 };
+
+/* Stage-level parameters of a first stage (token table [vocab, hidden], position table [seq, hidden]) and of
+ * a last stage (final LayerNorm gamma / beta [hidden], head matrix [hidden, vocab], no bias, not tied to the
+ * token table). */
+enum { ZB_SP_EMB_TOK = 0, ZB_SP_EMB_POS = 1, ZB_SP_LNF_G = 2, ZB_SP_LNF_B = 3, ZB_SP_W_HEAD = 4, ZB_SP_COUNT = 5 };
 
 /* `what` of zb_get_tensor / zb_set_tensor.  For the four per-parameter groups
  * add the param index (ZB_T_PARAM + ZB_P_WO ...); `layer` selects the layer and
@@ -75,6 +83,15 @@ enum {
   ZB_T_INPUT_DY = 65,  /* output gradient received from the next stage               get/set */
   ZB_T_OUTPUT_Y = 66,  /* activation sent to the next stage (written by F)           get */
   ZB_T_OUTPUT_DX = 67, /* input gradient sent to the previous stage (written by B)   get */
+  ZB_T_INPUT_IDS = 68,  /* first stage: token ids of microbatch mb; the host buffer holds int32 [tokens],
+                           bytes = 4 * tokens, every id in [0, vocab) (ZB_EINVAL otherwise)            get/set */
+  ZB_T_TARGET_IDS = 69, /* last stage: target ids, same format                                         get/set */
+  ZB_T_LOSS = 70,       /* last stage: mean over the tokens of microbatch mb of its cross-entropy loss
+                           (written by F), one fp32                                                    get */
+  ZB_T_STAGE_PARAM = 96,    /* + ZB_SP_*: stage-level master parameter (layer, mb ignored)              get/set */
+  ZB_T_STAGE_GRAD = 104,    /* + ZB_SP_*: its accumulated gradient                                      get/set */
+  ZB_T_STAGE_ADAM_M = 112,  /* + ZB_SP_*                                                                get/set */
+  ZB_T_STAGE_ADAM_V = 120,  /* + ZB_SP_*                                                                get/set */
   ZB_T_FLAT_PARAMS = 80, /* all master parameters of the stage, layer-major, param order, each
                             tensor padded to a multiple of 64 floats (zb_stage_flat_count)   get */
   ZB_T_FLAT_GRADS = 81, ZB_T_FLAT_ADAM_M = 82, ZB_T_FLAT_ADAM_V = 83
@@ -98,6 +115,16 @@ typedef struct {
                                half chunk 1; microbatch indices are then VIRTUAL, v = chunk * (m/2) + microbatch
                                for zb_begin_iteration's (even) m, each with its own INPUT_X / INPUT_DY /
                                OUTPUT_Y / OUTPUT_DX, and a pass on v runs through the layers of its chunk only */
+  int32_t role;             /* zb_role.  ZB_ROLE_FIRST: F of a microbatch starts from INPUT_IDS (X0 = token row +
+                               position row; INPUT_X is then written by F), W also adds the two tables' gradients
+                               (a table row receives the OUTPUT_DX rows of its tokens in increasing token order).
+                               ZB_ROLE_LAST: F ends with the final LayerNorm, the head and the softmax cross-entropy
+                               against TARGET_IDS (LOSS); B starts from the gradient of
+                               (1/m) * sum over the iteration's microbatches of their mean token loss (INPUT_DY is
+                               then written by B) and adds the final LayerNorm's gamma / beta gradients; W also adds
+                               the head's gradient.  Not with chunks = 2. */
+  int32_t vocab;            /* rows of the token table / columns of the head (first and last stage), <= 2^18;
+                               the first stage takes at most 8192 tokens per microbatch */
   float ln_eps;             /* 1e-5 */
   float lr, beta1, beta2, adam_eps, weight_decay; /* Algorithm 1's gamma, beta1, beta2, eps, lambda */
   float clip;               /* global gradient-norm clipping threshold (Sec. 4) */
@@ -306,7 +333,8 @@ zb_status zb_synchronize(zb_stage* st);
 const char* zb_last_error(const zb_stage* st); /* "" if none; valid until the next call on st */
 
 /* Model FLOPs of Table 1 for this stage and m microbatches: L*m*(F + B + W) with
- * F = sbh(24h+4s), B = sbh(24h+8s), W = 24sbh^2 (no causal discount). */
+ * F = sbh(24h+4s), B = sbh(24h+8s), W = 24sbh^2 (no causal discount); a last stage adds its head's three
+ * matmuls, m * 6 sbh * vocab (Table 1 covers transformer layers only). */
 zb_status zb_stage_model_flops(const zb_stage* st, int32_t m, double* flops);
 
 /* Activation bytes this stage really holds per microbatch, in the terms of Appendix G's memory model:

@@ -35,6 +35,10 @@ PARAM_INDEX = {n: i for i, n in enumerate(
 T_PARAM, T_GRAD, T_ADAM_M, T_ADAM_V = 0, 16, 32, 48
 T_INPUT_X, T_INPUT_DY, T_OUTPUT_Y, T_OUTPUT_DX = 64, 65, 66, 67
 T_FLAT_PARAMS, T_FLAT_GRADS, T_FLAT_ADAM_M, T_FLAT_ADAM_V = 80, 81, 82, 83
+T_INPUT_IDS, T_TARGET_IDS, T_LOSS = 68, 69, 70
+T_STAGE_PARAM, T_STAGE_GRAD, T_STAGE_ADAM_M, T_STAGE_ADAM_V = 96, 104, 112, 120
+ROLE = {"middle": 0, "first": 1, "last": 2}
+STAGE_PARAM_INDEX = {"emb_tok": 0, "emb_pos": 1, "lnf_g": 2, "lnf_b": 3, "w_head": 4}
 S_QKV_IN, S_PROJ_IN, S_FC1_IN, S_FC2_IN, S_QKV_DOUT, S_PROJ_DOUT, S_FC1_DOUT, S_FC2_DOUT = range(8)
 OUTCOME_NAMES = ("COMMITTED", "SKIPPED_LOCAL", "ROLLED_BACK_NONFINITE", "ROLLED_BACK_RECLIPPED",
                  "DEFERRED_CLIPPED", "DEFERRED_SKIPPED")
@@ -48,7 +52,8 @@ class zb_config(C.Structure):
     _fields_ = [("layers", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32), ("ffn", C.c_int32),
                 ("seq", C.c_int32), ("mb_size", C.c_int32), ("max_microbatches", C.c_int32),
                 ("max_pending_b", C.c_int32), ("max_pending_w", C.c_int32), ("max_inflight", C.c_int32),
-                ("dtype", C.c_int32), ("journal", C.c_int32), ("group_w", C.c_int32), ("fuse_bw", C.c_int32), ("chunks", C.c_int32), ("ln_eps", C.c_float), ("lr", C.c_float),
+                ("dtype", C.c_int32), ("journal", C.c_int32), ("group_w", C.c_int32), ("fuse_bw", C.c_int32), ("chunks", C.c_int32), ("role", C.c_int32), ("vocab", C.c_int32),
+                ("ln_eps", C.c_float), ("lr", C.c_float),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
                 ("weight_decay", C.c_float), ("clip", C.c_float), ("hip_stream", C.c_void_p),
                 ("arena", C.c_void_p), ("arena_bytes", C.c_size_t)]
@@ -293,7 +298,8 @@ class Stage:
     """One pipeline stage living on the current CUDA/HIP device."""
 
     def __init__(self, *, layers, hidden, heads, ffn, seq, mb_size=1, dtype="bf16", max_microbatches,
-                 max_pending_b, max_pending_w, max_inflight, journal=True, group_w=True, fuse_bw=False, chunks=1, ln_eps=1e-5, lr=1e-4, beta1=0.9,
+                 max_pending_b, max_pending_w, max_inflight, journal=True, group_w=True, fuse_bw=False, chunks=1,
+                 role="middle", vocab=0, ln_eps=1e-5, lr=1e-4, beta1=0.9,
                  beta2=0.95, adam_eps=1e-8, weight_decay=0.01, clip=1.0, device="cuda:0", stream=None):
         import torch
         if not torch.cuda.is_available():
@@ -310,6 +316,8 @@ class Stage:
         cfg.group_w = 1 if group_w else 0
         cfg.fuse_bw = 1 if fuse_bw else 0
         cfg.chunks = chunks
+        cfg.role, cfg.vocab = ROLE[role], vocab
+        self.role, self.vocab, self.seq = role, vocab, seq
         cfg.ln_eps, cfg.lr, cfg.beta1, cfg.beta2 = ln_eps, lr, beta1, beta2
         cfg.adam_eps, cfg.weight_decay, cfg.clip = adam_eps, weight_decay, clip
         need = C.c_size_t(0)
@@ -391,7 +399,37 @@ class Stage:
         return StepReport(rep.outcome, bool(rep.stepped_optimistically), rep.local_sq, rep.global_norm,
                           rep.clip_coef, rep.t, rep.alg1_mismatch_elems)
 
+    def stage_param_shape(self, index: int):
+        h, v = self.cfg.hidden, self.vocab
+        return [(v, h), (self.seq, h), (h,), (h,), (h, v)][index]
+
+    def set_ids(self, what: int, mb: int, ids):
+        """zb_set_tensor for T_INPUT_IDS / T_TARGET_IDS: int32 [tokens]."""
+        v = np.ascontiguousarray(ids, np.int32)
+        self._call(lib.zb_set_tensor, what, 0, mb, v.ctypes.data_as(C.c_void_p), v.nbytes)
+
+    def get_ids(self, what: int, mb: int) -> np.ndarray:
+        out = np.empty(self.tokens, np.int32)
+        self._call(lib.zb_get_tensor, what, 0, mb, out.ctypes.data_as(C.c_void_p), out.nbytes)
+        return out
+
+    def get_loss(self, mb: int) -> float:
+        out = np.empty(1, np.float32)
+        self._call(lib.zb_get_tensor, T_LOSS, 0, mb, out.ctypes.data_as(C.c_void_p), out.nbytes)
+        return float(out[0])
+
+    def set_stage_params(self, extra):
+        """extra: dict name -> fp32 array (emb_tok, emb_pos / lnf_g, lnf_b, w_head)."""
+        for name, value in extra.items():
+            self.set_tensor(T_STAGE_PARAM + STAGE_PARAM_INDEX[name], 0, 0, value)
+
+    def get_stage_group(self, base: int):
+        names = ("emb_tok", "emb_pos") if self.role == "first" else ("lnf_g", "lnf_b", "w_head")
+        return {n: self.get_tensor(base + STAGE_PARAM_INDEX[n]) for n in names}
+
     def _count(self, what: int) -> int:
+        if 96 <= what < 128:
+            return int(np.prod(self.stage_param_shape((what - 96) % 8)))
         if what < 64:
             shp = self.param_shape(what % 16)
             return int(np.prod(shp))
@@ -406,6 +444,8 @@ class Stage:
     def get_tensor(self, what: int, layer: int = 0, mb: int = 0) -> np.ndarray:
         out = np.empty(self._count(what), np.float32)
         self._call(lib.zb_get_tensor, what, layer, mb, out.ctypes.data_as(C.c_void_p), out.nbytes)
+        if 96 <= what < 128:
+            return out.reshape(self.stage_param_shape((what - 96) % 8))
         if what < 64:
             return out.reshape(self.param_shape(what % 16))
         if what < 80:

@@ -15,7 +15,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzbstage.so")
 
 SOURCES = ["stage.hip", "kernels_rowwise.hip", "kernels_optimizer.hip", "gemm_generic.hip", "gemm_mfma.hip",
-           "attention_generic.hip", "attention_mfma.hip", "attention_mfma128.hip", "autosched.hip"]
+           "attention_generic.hip", "attention_mfma.hip", "attention_mfma128.hip", "autosched.hip",
+           "kernels_endstage.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",

@@ -130,7 +130,8 @@ __device__ __forceinline__ void layernorm_bwd_dx_body(int row, const T* __restri
       float gam[kVec];
       Vec4<T>::load(g + off + col, gg[c]);
       Vec4<T>::load(x + off + col, xh[c]);
-      Vec4<T>::load(resid + off + col, rr[c]);
+      if (resid) Vec4<T>::load(resid + off + col, rr[c]);
+      else rr[c][0] = rr[c][1] = rr[c][2] = rr[c][3] = 0.f;
       Vec4<float>::load(gamma + col, gam);
 #pragma unroll
       for (int e = 0; e < kVec; ++e) {

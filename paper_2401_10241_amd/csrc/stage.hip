@@ -40,12 +40,12 @@ struct LayerOff {  // byte offsets inside one slot of each pool
 
 enum KClass {
   KC_GEMM_FWD = 0, KC_GEMM_DGRAD, KC_GEMM_WGRAD, KC_ATTN_FWD, KC_ATTN_BWD, KC_LN_FWD, KC_LN_BWD, KC_COLSUM,
-  KC_FILL, KC_SUMSQ, KC_ADAMW_STEP, KC_ADAMW_ROLLBACK, KC_ADAMW_RESTEP, KC_TRANSPOSE, KC_COUNT
+  KC_FILL, KC_SUMSQ, KC_ADAMW_STEP, KC_ADAMW_ROLLBACK, KC_ADAMW_RESTEP, KC_TRANSPOSE, KC_EMBED, KC_LOSS, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd", "layernorm_bwd",
     "bias_grad_colsum", "grad_zero_fill", "grad_sumsq", "adamw_step", "adamw_rollback", "adamw_restep",
-    "weight_transpose"};
+    "weight_transpose", "embedding", "cross_entropy"};
 
 struct ProfRec {
   int cls;
@@ -82,6 +82,16 @@ struct zb_stage {
   std::vector<int> free_fb, free_fw, free_bw, slot_fb, slot_fw, slot_bw;
   std::vector<unsigned char> done[3];
   int m = 0, iter = 0;
+
+  // first / last stage (Sec. 5.1)
+  int role = ZB_ROLE_MIDDLE, V = 0;
+  size_t spoff[ZB_SP_COUNT], spcount[ZB_SP_COUNT];  // stage-level tensors in the flat vectors (count 0: absent)
+  int *ids = nullptr, *perm = nullptr;  // [max_microbatches][T]: input ids (first) / target ids (last); sorted token order
+  float *loss = nullptr, *row_loss = nullptr;
+  size_t fb_logits = 0, fb_lse = 0, fb_statsf = 0, fw_z = 0, bw_dlogits = 0;  // last stage: offsets inside the stash slots
+  float* SP(int i) const { return theta + spoff[i]; }
+  float* SG(int i) const { return grad + spoff[i]; }
+  const void* SWt(int i) const { return bf16 ? (const void*)(theta16 + spoff[i]) : (const void*)SP(i); }
 
   char* tmp = nullptr;  // [T, h] activation-gradient scratch
   float *dvec = nullptr, *ln_partials = nullptr, *staging = nullptr, *gemm_ws = nullptr;
@@ -161,6 +171,13 @@ bool valid_shapes(const zb_config* c, std::string* why) {
   if ((long long)c->seq * c->mb_size > (1 << 24)) return bad("too many tokens per microbatch");
   if (c->chunks != 0 && c->chunks != 1 && c->chunks != 2) return bad("chunks must be 1 or 2");
   if (c->chunks == 2 && c->layers % 2 != 0) return bad("two chunks need an even number of layers");
+  if (c->role != ZB_ROLE_MIDDLE && c->role != ZB_ROLE_FIRST && c->role != ZB_ROLE_LAST) return bad("unknown role");
+  if (c->role != ZB_ROLE_MIDDLE) {
+    if (c->chunks == 2) return bad("a first or last stage cannot hold two chunks");
+    if (c->vocab < 1 || c->vocab > kEmbeddingMaxVocab) return bad("vocab must be in [1, 2^18]");
+    if (c->role == ZB_ROLE_FIRST && (long long)c->seq * c->mb_size > kEmbeddingMaxTokens)
+      return bad("a first stage takes at most 8192 tokens per microbatch");
+  }
   return true;
 }
 
@@ -184,6 +201,18 @@ size_t layout(zb_stage* st, void* arena) {
       st->poff[l * ZB_P_COUNT + i] = o;
       o += align_up(pc[i], 64);
     }
+  st->role = c.role;
+  st->V = c.role == ZB_ROLE_MIDDLE ? 0 : c.vocab;
+  for (int i = 0; i < ZB_SP_COUNT; ++i) st->spoff[i] = st->spcount[i] = 0;
+  auto stage_tensor = [&](int i, size_t n) { st->spcount[i] = n; st->spoff[i] = o; o += align_up(n, 64); };
+  if (c.role == ZB_ROLE_FIRST) {
+    stage_tensor(ZB_SP_EMB_TOK, (size_t)st->V * h);
+    stage_tensor(ZB_SP_EMB_POS, (size_t)st->s * h);
+  } else if (c.role == ZB_ROLE_LAST) {
+    stage_tensor(ZB_SP_LNF_G, h);
+    stage_tensor(ZB_SP_LNF_B, h);
+    stage_tensor(ZB_SP_W_HEAD, h * (size_t)st->V);
+  }
   st->flat_count = o;
 
   Bump bp(arena);
@@ -231,11 +260,24 @@ size_t layout(zb_stage* st, void* arena) {
     q.bw_dfh = put(obw, T * f * E);
     q.bw_dy = put(obw, l == st->L - 1 ? 0 : T * h * E);
   }
+  if (c.role == ZB_ROLE_LAST) {  // the head: logits and row statistics F -> B, its input F -> W, its output gradient B -> W
+    st->fb_logits = put(ofb, T * (size_t)st->V * E);
+    st->fb_lse = put(ofb, T * sizeof(float));
+    st->fb_statsf = put(ofb, T * 2 * sizeof(float));
+    st->fw_z = put(ofw, T * h * E);
+    st->bw_dlogits = put(obw, T * (size_t)st->V * E);
+  }
   st->fb_slot = ofb; st->fw_slot = ofw; st->bw_slot = obw;
   st->fb_pool = bp.take<char>(ofb * (size_t)c.max_pending_b);
   st->fw_pool = bp.take<char>(ofw * (size_t)c.max_inflight);
   st->bw_pool = bp.take<char>(obw * (size_t)c.max_pending_w);
 
+  if (c.role != ZB_ROLE_MIDDLE) st->ids = bp.take<int>((size_t)c.max_microbatches * T * sizeof(int));
+  if (c.role == ZB_ROLE_FIRST) st->perm = bp.take<int>((size_t)c.max_microbatches * T * sizeof(int));
+  if (c.role == ZB_ROLE_LAST) {
+    st->loss = bp.take<float>((size_t)c.max_microbatches * sizeof(float));
+    st->row_loss = bp.take<float>(T * sizeof(float));
+  }
   st->tmp = bp.take<char>(T * h * E);
   st->dvec = bp.take<float>((size_t)st->b * st->a * st->s * sizeof(float));
   {  // LayerNorm-backward partials; the bias-gradient column sums reuse it for their row slices
@@ -352,6 +394,13 @@ template <typename T> struct Exec {
     const double E = sizeof(T);
     int l_lo, l_hi;
     layer_range(st, mb, &l_lo, &l_hi);
+    if (st->role == ZB_ROLE_FIRST) {  // X0 = token row + position row, written where a middle stage receives X
+      const int* ids = st->ids + (size_t)mb * T_;
+      ProfScope ps(st, KC_EMBED, 0, 3 * E * T_ * h);
+      ZB_HIP(st, launch_embedding_fwd<T>(ids, (const T*)st->SWt(ZB_SP_EMB_TOK), (const T*)st->SWt(ZB_SP_EMB_POS),
+                                         (T*)(st->in_x + st->act_bytes * (size_t)mb), T_, h, st->s, s));
+      ZB_HIP(st, launch_sort_tokens(ids, st->perm + (size_t)mb * T_, T_, s));  // for the table's gradient in W
+    }
     for (int l = l_lo; l <= l_hi; ++l) {
       const LayerOff& q = st->lo[l];
       T* A = (T*)(fw + q.fw_a);
@@ -403,6 +452,80 @@ template <typename T> struct Exec {
       ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
       x = y;
     }
+    if (st->role == ZB_ROLE_LAST) {  // final LayerNorm, head, softmax cross-entropy against the targets
+      T* Z = (T*)(fw + st->fw_z);
+      T* logits = (T*)(fb + st->fb_logits);
+      {
+        ProfScope ps(st, KC_LN_FWD, 0, 2 * E * T_ * h + 8.0 * T_);
+        ZB_HIP(st, launch_layernorm_fwd<T>(x, st->SP(ZB_SP_LNF_G), st->SP(ZB_SP_LNF_B), Z, (float*)(fb + st->fb_statsf),
+                                            T_, h, st->cfg.ln_eps, s));
+      }
+      GemmArgs g{};
+      g.A = Z; g.B = st->SWt(ZB_SP_W_HEAD); g.M = T_; g.N = st->V; g.K = h;
+      g.a_sm = h; g.a_sk = 1; g.b_sk = st->V; g.b_sn = 1;
+      g.epilogue = EPI_STORE; g.out0 = logits;
+      ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
+      ProfScope ps(st, KC_LOSS, 0, E * T_ * (double)st->V);
+      ZB_HIP(st, launch_ce_fwd<T>(logits, st->ids + (size_t)mb * T_, (float*)(fb + st->fb_lse), st->row_loss,
+                                  st->loss + mb, T_, st->V, s));
+    }
+    return ZB_OK;
+  }
+
+  // Last stage: the gradient that starts B.  dLogits = (softmax - onehot) / (tokens * m) is kept for W, goes
+  // through the head and the final LayerNorm, and lands where a middle stage receives the upstream gradient.
+  static zb_status head_backward(zb_stage* st, int mb) {
+    const int h = st->h, T_ = st->T;
+    hipStream_t s = st->stream;
+    char* fb = st->fb_pool + st->fb_slot * (size_t)st->slot_fb[mb];
+    char* bw = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mb];
+    const double E = sizeof(T);
+    T* dlogits = (T*)(bw + st->bw_dlogits);
+    {
+      ProfScope ps(st, KC_LOSS, 0, 2 * E * T_ * (double)st->V);
+      ZB_HIP(st, launch_ce_bwd<T>((const T*)(fb + st->fb_logits), (const float*)(fb + st->fb_lse),
+                                  st->ids + (size_t)mb * T_, dlogits, T_, st->V, 1.0f / ((float)T_ * (float)st->m), s));
+    }
+    GemmArgs g{};  // dZ = dLogits W_head^T
+    g.A = dlogits; g.M = T_; g.N = h; g.K = st->V;
+    g.a_sm = st->V; g.a_sk = 1;
+    if (st->bf16) { g.B = st->theta16_t + st->spoff[ZB_SP_W_HEAD]; g.b_sk = h; g.b_sn = 1; }
+    else { g.B = st->SP(ZB_SP_W_HEAD); g.b_sk = 1; g.b_sn = st->V; }
+    g.epilogue = EPI_STORE; g.out0 = st->tmp;
+    ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
+    ProfScope ps(st, KC_LN_BWD, 0, 3 * E * T_ * h);
+    ZB_HIP(st, launch_layernorm_bwd<T>((const T*)st->tmp, (const T*)(st->out_y + st->act_bytes * (size_t)mb),
+                                        (const float*)(fb + st->fb_statsf), st->SP(ZB_SP_LNF_G), (const T*)nullptr,
+                                        (T*)(st->in_dy + st->act_bytes * (size_t)mb), st->SG(ZB_SP_LNF_G),
+                                        st->SG(ZB_SP_LNF_B), st->ln_partials, T_, h, s));
+    return ZB_OK;
+  }
+
+  // Stage-level parameter gradients of the W pass of n microbatches (in the order given): the head's weight
+  // gradient (last stage), the token and position tables' gradients (first stage).
+  static zb_status end_stage_wgrad(zb_stage* st, const int* mbs, int n) {
+    const int h = st->h, T_ = st->T;
+    hipStream_t s = st->stream;
+    const double E = sizeof(T);
+    if (st->role == ZB_ROLE_LAST) {
+      WgradMultiArgs w{};
+      w.nprob = 1; w.ngroup = n; w.K = T_;
+      w.M[0] = h; w.N[0] = st->V; w.outf[0] = st->SG(ZB_SP_W_HEAD);
+      for (int i = 0; i < n; ++i) {
+        w.a[i] = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mbs[i]] + st->fw_z;
+        w.b[i] = st->bw_pool + st->bw_slot * (size_t)st->slot_bw[mbs[i]] + st->bw_dlogits;
+      }
+      ProfScope ps(st, KC_GEMM_WGRAD, 2.0 * h * st->V * T_ * n, 8.0 * h * st->V + E * (double)T_ * ((double)h + st->V) * n);
+      ZB_HIP(st, launch_wgrad_multi<T>(w, s));
+    } else if (st->role == ZB_ROLE_FIRST) {
+      for (int i = 0; i < n; ++i) {
+        const int mb = mbs[i];
+        ProfScope ps(st, KC_EMBED, 0, 2 * E * T_ * h + 8.0 * T_ * h);
+        ZB_HIP(st, launch_embedding_grad<T>((const T*)(st->out_dx + st->act_bytes * (size_t)mb),
+                                            st->ids + (size_t)mb * T_, st->perm + (size_t)mb * T_,
+                                            st->SG(ZB_SP_EMB_TOK), st->SG(ZB_SP_EMB_POS), T_, h, st->s, s));
+      }
+    }
     return ZB_OK;
   }
 
@@ -418,6 +541,10 @@ template <typename T> struct Exec {
     int bottom, top;  // the layers this (virtual) microbatch runs through
     layer_range(st, mb, &bottom, &top);
     if (l_hi < 0) { l_hi = top; l_lo = bottom; }
+    if (st->role == ZB_ROLE_LAST && l_hi == top) {
+      zb_status rc = head_backward(st, mb);
+      if (rc != ZB_OK) return rc;
+    }
     for (int l = l_hi; l >= l_lo; --l) {
       const LayerOff& q = st->lo[l];
       // gradient entering layer l: the upstream gradient, or what layer l+1 left in the B->W stash
@@ -543,8 +670,17 @@ template <typename T> struct Exec {
   }
 
   static zb_status backward_weight(zb_stage* st, int mb, int l_hi = -1, int l_lo = 0) {
-    if (l_hi < 0) layer_range(st, mb, &l_lo, &l_hi);
-    return wgrad_layers(st, &mb, 1, l_hi, l_lo);
+    int bottom, top;
+    layer_range(st, mb, &bottom, &top);
+    if (l_hi < 0) { l_hi = top; l_lo = bottom; }
+    if (st->role == ZB_ROLE_LAST && l_hi == top) {
+      zb_status rc = end_stage_wgrad(st, &mb, 1);
+      if (rc != ZB_OK) return rc;
+    }
+    zb_status rc = wgrad_layers(st, &mb, 1, l_hi, l_lo);
+    if (rc != ZB_OK) return rc;
+    if (st->role == ZB_ROLE_FIRST && l_lo == bottom) rc = end_stage_wgrad(st, &mb, 1);
+    return rc;
   }
 
   // The traditional single backward (Sec. 1): layer by layer, the input gradient and right after it the
@@ -564,7 +700,14 @@ template <typename T> struct Exec {
   static zb_status backward_weight_group(zb_stage* st, const int* mbs, int n) {
     int bottom, top;
     layer_range(st, mbs[0], &bottom, &top);
-    return wgrad_layers(st, mbs, n, top, bottom);
+    if (st->role == ZB_ROLE_LAST) {
+      zb_status rc = end_stage_wgrad(st, mbs, n);
+      if (rc != ZB_OK) return rc;
+    }
+    zb_status rc = wgrad_layers(st, mbs, n, top, bottom);
+    if (rc != ZB_OK) return rc;
+    if (st->role == ZB_ROLE_FIRST) rc = end_stage_wgrad(st, mbs, n);
+    return rc;
   }
 };
 
@@ -593,6 +736,8 @@ struct TensorRef {
   bool writable;
   bool is_param;   // also refresh the bf16 working copy
   size_t flat_off;
+  bool is_ids;     // int32 token / target ids (host buffer int32 as well)
+  int matrix_rows, matrix_cols;  // parameter that also has a transposed bf16 copy (0: none)
 };
 
 zb_status resolve(zb_stage* st, int what, int layer, int mb, TensorRef* r) {
@@ -608,6 +753,7 @@ zb_status resolve(zb_stage* st, int what, int layer, int mb, TensorRef* r) {
     r->ptr = base + r->flat_off;
     r->count = st->pcount[i];
     r->is_param = grp == 0;
+    if (grp == 0 && (i == ZB_P_WQKV || i == ZB_P_WO || i == ZB_P_W1 || i == ZB_P_W2)) weight_dims(st, i, &r->matrix_rows, &r->matrix_cols);
     return ZB_OK;
   }
   if (what >= ZB_T_INPUT_X && what <= ZB_T_OUTPUT_DX) {
@@ -618,6 +764,34 @@ zb_status resolve(zb_stage* st, int what, int layer, int mb, TensorRef* r) {
     r->ptr = base + st->act_bytes * (size_t)mb;
     r->count = (size_t)st->T * st->h;
     r->writable = what == ZB_T_INPUT_X || what == ZB_T_INPUT_DY;
+    return ZB_OK;
+  }
+  if (what == ZB_T_INPUT_IDS || what == ZB_T_TARGET_IDS) {
+    if ((what == ZB_T_INPUT_IDS) != (st->role == ZB_ROLE_FIRST) || st->role == ZB_ROLE_MIDDLE)
+      return fail(st, ZB_EINVAL, "input ids belong to a first stage, target ids to a last stage");
+    if (mb < 0 || mb >= st->cfg.max_microbatches) return fail(st, ZB_EINVAL, "microbatch out of range");
+    r->ptr = st->ids + (size_t)mb * st->T;
+    r->count = (size_t)st->T;
+    r->is_ids = true;
+    return ZB_OK;
+  }
+  if (what == ZB_T_LOSS) {
+    if (st->role != ZB_ROLE_LAST) return fail(st, ZB_EINVAL, "only a last stage computes a loss");
+    if (mb < 0 || mb >= st->cfg.max_microbatches) return fail(st, ZB_EINVAL, "microbatch out of range");
+    r->ptr = st->loss + mb;
+    r->count = 1;
+    r->writable = false;
+    return ZB_OK;
+  }
+  if (what >= ZB_T_STAGE_PARAM && what < ZB_T_STAGE_ADAM_V + 8) {
+    const int grp = (what - ZB_T_STAGE_PARAM) / 8, i = (what - ZB_T_STAGE_PARAM) % 8;
+    if (i >= ZB_SP_COUNT || st->spcount[i] == 0) return fail(st, ZB_EINVAL, "this stage has no such stage-level parameter");
+    float* base = grp == 0 ? st->theta : grp == 1 ? st->grad : grp == 2 ? st->adam_m : st->adam_v;
+    r->flat_off = st->spoff[i];
+    r->ptr = base + r->flat_off;
+    r->count = st->spcount[i];
+    r->is_param = grp == 0;
+    if (grp == 0 && i == ZB_SP_W_HEAD) { r->matrix_rows = st->h; r->matrix_cols = st->V; }
     return ZB_OK;
   }
   if (what >= ZB_T_FLAT_PARAMS && what <= ZB_T_FLAT_ADAM_V) {
@@ -956,6 +1130,9 @@ zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, z
     ProfScope ps(st, KC_TRANSPOSE, 0, 4.0 * 12.0 * st->h * (double)st->h * st->L);
     for (int l = 0; l < st->L; ++l)
       for (int wi : kMatrices) ZB_HIP(st, refresh_transposed(st, l, wi));
+    if (st->role == ZB_ROLE_LAST)
+      ZB_HIP(st, launch_transpose_bf16(st->theta16 + st->spoff[ZB_SP_W_HEAD], st->theta16_t + st->spoff[ZB_SP_W_HEAD],
+                                       st->h, st->V, s));
   }
   if (report) {
     OptDevState h;
@@ -1000,6 +1177,11 @@ zb_status zb_set_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, c
   if (!r.writable) return fail(st, ZB_EINVAL, "tensor is read-only");
   if (bytes != r.count * sizeof(float)) return fail(st, ZB_EINVAL, "bytes must be 4 * element count");
   hipStream_t s = st->stream;
+  if (r.is_ids) {  // checked on the host: a kernel indexes the tables / the logits with these
+    const int32_t* ids = (const int32_t*)host_src;
+    for (size_t i = 0; i < r.count; ++i)
+      if (ids[i] < 0 || ids[i] >= st->V) return fail(st, ZB_EINVAL, "id outside [0, vocab)");
+  }
   if (r.typed && st->bf16) {
     if (r.count > st->staging_floats) return fail(st, ZB_ESTATE, "staging buffer too small");
     ZB_HIP(st, hipMemcpyAsync(st->staging, host_src, bytes, hipMemcpyHostToDevice, s));
@@ -1008,8 +1190,9 @@ zb_status zb_set_tensor(zb_stage* st, int32_t what, int32_t layer, int32_t mb, c
     ZB_HIP(st, hipMemcpyAsync(r.ptr, host_src, bytes, hipMemcpyHostToDevice, s));
     if (r.is_param && st->bf16) {
       ZB_HIP(st, launch_convert_from_f32<bf16_t>((const float*)r.ptr, st->theta16 + r.flat_off, r.count, s));
-      const int pi = what % 16;
-      if (pi == ZB_P_WQKV || pi == ZB_P_WO || pi == ZB_P_W1 || pi == ZB_P_W2) ZB_HIP(st, refresh_transposed(st, layer, pi));
+      if (r.matrix_rows)  // the dgrad GEMMs read this matrix transposed
+        ZB_HIP(st, launch_transpose_bf16(st->theta16 + r.flat_off, st->theta16_t + r.flat_off, r.matrix_rows,
+                                         r.matrix_cols, s));
     }
   }
   ZB_HIP(st, hipStreamSynchronize(s));
@@ -1087,6 +1270,7 @@ zb_status zb_stage_model_flops(const zb_stage* st, int32_t m, double* flops) {
   const double s = st->s, b = st->b, h = st->h;
   const double F = s * b * h * (24 * h + 4 * s), B = s * b * h * (24 * h + 8 * s), W = s * b * h * 24 * h;
   *flops = (double)(st->L / st->chunks) * m * (F + B + W);  // with two chunks m counts virtual microbatches
+  if (st->role == ZB_ROLE_LAST) *flops += (double)m * 6.0 * s * b * h * (double)st->V;
   return ZB_OK;
 }
 

@@ -120,7 +120,7 @@ template <typename T> hipError_t launch_attention_bwd(const AttnArgs& a, hipStre
 template <typename T>
 hipError_t launch_layernorm_fwd(const T* x, const float* gamma, const float* beta, T* out, float* stats,
                                 int rows, int h, float eps, hipStream_t s);
-// dx = resid + LNbwd(g); partial dgamma/dbeta of up to kLnBwdSlices row slices go to `partials`
+// dx = resid + LNbwd(g) (resid may be null: no residual path); partial dgamma/dbeta of up to kLnBwdSlices row slices go to `partials`
 // ([slices][2][h]) and are then added to dgamma/dbeta in slice order.
 template <typename T>
 hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, const float* gamma, const T* resid,
@@ -152,6 +152,30 @@ template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStr
 template <typename T>
 hipError_t launch_gather_columns(const T* src, long ld, int rows, const int* cols, int ncols, float* dst,
                                  hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// first / last stage (Sec. 5.1): embedding lookup and its gradients, softmax cross-entropy
+// ---------------------------------------------------------------------------------------
+constexpr int kEmbeddingMaxTokens = 8192;  // tokens per microbatch the token sort takes (keys id * 8192 + t)
+constexpr int kEmbeddingMaxVocab = 1 << 18;
+// out[t] = tok[ids[t]] + pos[t mod seq], rows of h elements
+template <typename T>
+hipError_t launch_embedding_fwd(const int* ids, const T* tok, const T* pos, T* out, int tokens, int h, int seq,
+                                hipStream_t s);
+// perm = token indices ordered by (id, token index)
+hipError_t launch_sort_tokens(const int* ids, int* perm, int tokens, hipStream_t s);
+// g_tok[v] += sum of dx[t] over the tokens with ids[t] = v (increasing t); g_pos[p] += sum over the sequences
+template <typename T>
+hipError_t launch_embedding_grad(const T* dx, const int* ids, const int* perm, float* g_tok, float* g_pos, int tokens,
+                                 int h, int seq, hipStream_t s);
+// lse[r] = log sum exp of row r; row_loss[r] = lse[r] - logits[r, targets[r]]; *loss_out = mean of row_loss
+template <typename T>
+hipError_t launch_ce_fwd(const T* logits, const int* targets, float* lse, float* row_loss, float* loss_out, int rows,
+                         int vocab, hipStream_t s);
+// dlogits[r, j] = scale * (exp(logits[r, j] - lse[r]) - [j == targets[r]])
+template <typename T>
+hipError_t launch_ce_bwd(const T* logits, const float* lse, const int* targets, T* dlogits, int rows, int vocab,
+                         float scale, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // optimizer (Sec. 4 and Appendix C).  All decisions live in OptDevState on the device.

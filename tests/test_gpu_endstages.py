@@ -1,0 +1,212 @@
+"""GPU parity of the first and the last pipeline stage (Sec. 5.1: embedding lookup in the first, loss in the
+last, one transformer layer fewer in both) against oracle/endstages.py, through the C ABI."""
+import numpy as np
+import pytest
+
+import zb_inputs
+from oracle import endstages as E
+from oracle import optimizer as O
+from oracle.schedule import stage_order
+from oracle.stage import PARAM_ORDER
+from zb_testlib import TOL, check_delta_theta, check_tensor, hyper, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+W = zb_inputs.Workload
+
+
+def build(w, role, vocab, m=None, pools=None, **kw):
+    import paper_2401_10241_amd as zb
+    m = m or w.m
+    pb, pw, fl = pools or zb.schedule_stash_need(w.p, w.stage, m, w.kind)
+    params = zb_inputs.stage_params(w)
+    extra = zb_inputs.end_stage_params(w, role, vocab)
+    dev = zb.Stage(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
+                   dtype=w.dtype, max_microbatches=m, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
+                   role=role, vocab=vocab, ln_eps=w.ln_eps, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
+                   adam_eps=w.adam_eps, weight_decay=w.weight_decay, clip=w.clip, **kw)
+    dev.set_params(params)
+    dev.set_stage_params(extra)
+    orc = E.EndStageOracle(role=role, vocab=vocab, extra_params=extra, layers=w.layers, hidden=w.hidden,
+                           heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size, dtype=w.dtype, ln_eps=w.ln_eps,
+                           hyper=hyper(w), params=params)
+    return dev, orc
+
+
+def load(w, role, vocab, it, m, dev=None, orc=None):
+    import paper_2401_10241_amd as zb
+    for k in range(m):
+        if role == "first":
+            ids = zb_inputs.token_ids(w, it, k, vocab)
+            dY = zb_inputs.upstream_grad(w, it, k)
+            if dev is not None:
+                dev.set_ids(zb.T_INPUT_IDS, k, ids)
+                dev.set_tensor(zb.T_INPUT_DY, 0, k, dY)
+            if orc is not None:
+                orc.set_ids(k, ids)
+                orc.set_upstream_grad(k, dY)
+        else:
+            X = zb_inputs.stage_input(w, it, k)
+            tg = zb_inputs.target_ids(w, it, k, vocab)
+            if dev is not None:
+                dev.set_tensor(zb.T_INPUT_X, 0, k, X)
+                dev.set_ids(zb.T_TARGET_IDS, k, tg)
+            if orc is not None:
+                orc.set_input(k, X)
+                orc.set_targets(k, tg)
+
+
+def compare(w, role, dev, orc, m):
+    import paper_2401_10241_amd as zb
+    tol = TOL[w.dtype]
+    worst = 0.0
+    for k in range(m):
+        e, _ = check_tensor(f"dX[{k}]", dev.get_tensor(zb.T_OUTPUT_DX, 0, k), orc.dX[k], tol, w.dtype)
+        worst = max(worst, e)
+        if role == "first":
+            e, _ = check_tensor(f"Y[{k}]", dev.get_tensor(zb.T_OUTPUT_Y, 0, k), orc.Y[k], tol, w.dtype)
+            worst = max(worst, e)
+        else:
+            # the loss is a mean of log-probabilities: absolute error of the bf16 logits' rounding, far below tol
+            assert dev.get_loss(k) == pytest.approx(orc.loss[k], rel=tol, abs=0)
+    got = dev.get_group(zb.T_GRAD)
+    for l in range(w.layers):
+        for name in PARAM_ORDER:
+            e, _ = check_tensor(f"grad {l} {name}", got[l][name], orc.grads[l][name], tol, "fp32")
+            worst = max(worst, e)
+    for name, g in dev.get_stage_group(zb.T_STAGE_GRAD).items():
+        ref = orc.grads[orc.nl][name]
+        if name == "w_head":   # a column is the gradient of one vocabulary entry: the targets' columns carry the
+            g, ref = g.T, ref.T   # one-hot term and are far larger than the others, so the bound goes column by column
+        e, _ = check_tensor(f"grad {name}", g, ref, tol, "fp32", by_row=(name in ("emb_tok", "w_head")))
+        worst = max(worst, e)
+    return worst
+
+
+CASES = [
+    # role, dtype, layers, hidden, heads, ffn, seq, b, vocab, m      what the shape reaches
+    ("first", "fp32", 1, 64, 2, 256, 32, 2, 97, 3),          # generic kernels, odd vocabulary
+    ("first", "bf16", 2, 256, 4, 1024, 128, 1, 1000, 4),     # MFMA layers; ids repeat within a microbatch
+    ("last", "fp32", 1, 64, 2, 256, 32, 2, 97, 3),           # generic GEMMs for the head (vocab 97)
+    ("last", "bf16", 2, 256, 4, 1024, 128, 1, 1024, 4),      # head on the MFMA kernels (vocab a multiple of 256)
+    ("last", "bf16", 1, 512, 4, 2048, 256, 2, 5000, 2),      # bf16 head on the generic kernels (vocab 5000)
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "%s_%s_L%d_h%d_a%d_f%d_s%d_b%d_V%d_m%d" % c)
+def test_end_stage_parity(case):
+    import paper_2401_10241_amd as zb
+    role, dtype, layers, hidden, heads, ffn, seq, b, vocab, m = case
+    p = 4
+    sigma = 0 if role == "first" else p - 1
+    w = W("end", dtype, layers, hidden, heads, ffn, seq, b, p, sigma, m, "H1", seed=61 + hidden, lr=1e-3)
+    dev, orc = build(w, role, vocab)
+    dev.begin_iteration(0, m)
+    orc.begin_iteration(m)
+    load(w, role, vocab, 0, m, dev, orc)
+    dev.run_schedule(p, sigma, m, "H1")
+    dev.synchronize()
+    orc.run(stage_order(p, sigma, m, "H1"))
+    worst = compare(w, role, dev, orc, m)
+    # validated AdamW over the layers' and the stage-level parameters
+    before = dev.get_stage_group(zb.T_STAGE_PARAM)
+    ref_before = {k: v.copy() for k, v in orc.master[orc.nl].items()}
+    rep = dev.optimizer_step_validated(0.0, 0.0)
+    ref = orc.optimizer_step(O.GlobalState(0.0, 0.0))
+    assert rep.outcome == ref.outcome and rep.t == 1
+    after = dev.get_stage_group(zb.T_STAGE_PARAM)
+    tol = TOL[dtype]
+    for name in after:
+        if name != "lnf_b":   # starts at zero: its first update is lr * sign(g), see the optimizer tests
+            check_tensor(f"theta {name}", after[name], orc.master[orc.nl][name], tol, "fp32")
+        check_delta_theta(f"update {name}", before[name], after[name], ref_before[name], orc.master[orc.nl][name],
+                          orc.adam_v[orc.nl][name], max(tol, 1e-3))
+    # the next iteration runs on the updated tables / head (the bf16 working copies and the transposed head)
+    dev.begin_iteration(1, m)
+    orc.begin_iteration(m)
+    load(w, role, vocab, 1, m, dev, orc)
+    dev.run_schedule(p, sigma, m, "H1")
+    dev.synchronize()
+    orc.run(stage_order(p, sigma, m, "H1"))
+    worst = max(worst, compare(w, role, dev, orc, m))
+    print(f"[{role} {dtype} h={hidden} V={vocab}] worst rel-fro {worst:.2e}", flush=True)
+    dev.close()
+
+
+@pytest.mark.parametrize("role", ["first", "last"])
+def test_end_stage_gradients_are_bitwise_identical_across_orders_and_groupings(role):
+    import paper_2401_10241_amd as zb
+    m, p = 6, 4
+    sigma = 0 if role == "first" else p - 1
+    w = W("end_det", "bf16", 2, 256, 4, 1024, 128, 1, p, sigma, m, "H1", seed=67)
+    vocab = 512
+    results = []
+    flat = [(0, k) for k in range(m)] + [(1, k) for k in range(m)] + [(2, k) for k in range(m)]
+    for mode in ("H1 grouped", "H1 one by one", "flat", "1F1B fused", "W held back in groups of 3"):
+        dev, _ = build(w, role, vocab, pools=(m, m, m), **({"fuse_bw": True} if mode == "1F1B fused" else {}))
+        dev.begin_iteration(0, m)
+        load(w, role, vocab, 0, m, dev)
+        if mode == "H1 grouped":
+            dev.run_schedule(p, sigma, m, "H1")
+        elif mode == "1F1B fused":
+            dev.run_schedule(p, sigma, m, "1F1B")
+        elif mode.startswith("W held"):
+            dev.run_order(zb.order_group_w(zb.schedule_order(p, sigma, m, "H1"), 3))
+        else:
+            for c, k in (flat if mode == "flat" else zb.schedule_order(p, sigma, m, "H1")):
+                (dev.forward, dev.backward_input, dev.backward_weight)[c](k)
+        dev.synchronize()
+        results.append((dev.get_tensor(zb.T_FLAT_GRADS).copy(),
+                        [dev.get_tensor(zb.T_OUTPUT_DX, 0, k).copy() for k in range(m)]))
+        dev.close()
+    assert np.abs(results[0][0]).max() > 0
+    for g, dxs in results[1:]:
+        assert g.tobytes() == results[0][0].tobytes()
+        for a, b in zip(dxs, results[0][1]):
+            assert a.tobytes() == b.tobytes()
+
+
+def test_end_stage_argument_checks():
+    import paper_2401_10241_amd as zb
+    w = W("end_err", "fp32", 1, 64, 2, 256, 32, 1, 4, 0, 2, "H1", seed=3)
+    dev, _ = build(w, "first", 50)
+    with pytest.raises(zb.ZbError) as e:
+        dev.set_ids(zb.T_INPUT_IDS, 0, np.full(32, 50, np.int32))        # id == vocab
+    assert e.value.status == zb.EINVAL
+    with pytest.raises(zb.ZbError) as e:
+        dev.set_ids(zb.T_TARGET_IDS, 0, np.zeros(32, np.int32))          # targets belong to a last stage
+    assert e.value.status == zb.EINVAL
+    with pytest.raises(zb.ZbError) as e:
+        dev.get_loss(0)
+    assert e.value.status == zb.EINVAL
+    ids = zb_inputs.token_ids(w, 0, 0, 50)
+    dev.set_ids(zb.T_INPUT_IDS, 0, ids)
+    assert np.array_equal(dev.get_ids(zb.T_INPUT_IDS, 0), ids)
+    dev.close()
+    with pytest.raises(zb.ZbError):      # a first stage with two chunks
+        zb.Stage(layers=2, hidden=64, heads=2, ffn=256, seq=32, max_microbatches=2, max_pending_b=2,
+                 max_pending_w=2, max_inflight=2, role="first", vocab=50, chunks=2)
+    with pytest.raises(zb.ZbError):      # no vocabulary
+        zb.Stage(layers=1, hidden=64, heads=2, ffn=256, seq=32, max_microbatches=2, max_pending_b=2,
+                 max_pending_w=2, max_inflight=2, role="last", vocab=0)
+
+
+@pytest.mark.parametrize("role", ["first", "last"])
+def test_end_stage_at_the_14_6b_models_shapes(role):
+    # Sec. 5.1's 14.6B model: hidden 5120, 40 heads, sequence 1024, microbatch size 1; a GPT-3-like vocabulary
+    # (50257 entries) padded to a multiple of 256.  One layer and two microbatches keep the oracle at seconds.
+    import paper_2401_10241_amd as zb
+    vocab, m, p = 50432, 2, 16
+    sigma = 0 if role == "first" else p - 1
+    w = W("end_c4", "bf16", 1, 5120, 40, 20480, 1024, 1, p, sigma, m, "H1", seed=71)
+    dev, orc = build(w, role, vocab)
+    dev.begin_iteration(0, m)
+    orc.begin_iteration(m)
+    load(w, role, vocab, 0, m, dev, orc)
+    dev.run_schedule(p, sigma, m, "H1")
+    dev.synchronize()
+    orc.run(stage_order(p, sigma, m, "H1"))
+    worst = compare(w, role, dev, orc, m)
+    print(f"[{role} stage, 14.6B shapes, V={vocab}] worst rel-fro {worst:.2e}"
+          + (f", losses {[round(dev.get_loss(k), 4) for k in range(m)]}" if role == "last" else ""), flush=True)
+    dev.close()
