@@ -490,6 +490,23 @@ bool try_split_k(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipError_
   p.outf = g.workspace;
   *err = run_cfg<256, 4, EPI_PARTIAL, 3>(p, lda, ldb, s, slices);
   if (*err != hipSuccess) return true;
+  // The last step owns whole rows: a LayerNorm on those rows rides along instead of running as a kernel of
+  // its own on the stored result.
+  const bool ln_shape = g.ln_done && g.N <= 8192;
+  if (MODE == EPI_BIAS_RESID && g.ln_mode == 1 && ln_shape) {
+    *err = launch_splitk_layernorm_fwd<bf16_t>(g.workspace, slices, plane, g.bias, (const bf16_t*)g.aux,
+                                               (bf16_t*)g.out0, g.ln_gamma, g.ln_beta, (bf16_t*)g.ln_out, g.ln_stats,
+                                               g.M, g.N, g.ln_eps, s);
+    *g.ln_done = *err == hipSuccess;
+    return true;
+  }
+  if (MODE == EPI_STORE && g.ln_mode == 2 && ln_shape) {
+    *err = launch_splitk_layernorm_bwd<bf16_t>(g.workspace, slices, plane, (bf16_t*)g.out0, (const bf16_t*)g.ln_x, g.ln_stats,
+                                               g.ln_gamma, (const bf16_t*)g.ln_resid, (bf16_t*)g.ln_out, g.ln_dgamma,
+                                               g.ln_dbeta, g.ln_partials, g.M, g.N, s);
+    *g.ln_done = *err == hipSuccess;
+    return true;
+  }
   const size_t threads = plane / 4;
   gemm_splitk_fixup_kernel<MODE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(g.workspace, slices, plane, g.N,
                                                                                  make_epi(g));

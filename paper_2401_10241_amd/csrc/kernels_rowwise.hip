@@ -99,6 +99,75 @@ __global__ __launch_bounds__(kThreads) void layernorm_fwd_kernel(const T* __rest
   }
 }
 
+// LayerNorm forward fused with the end of a split-K GEMM whose output it normalises: the row's GEMM result is
+// the sum of `slices` fp32 planes (added in slice order) + bias + residual, rounded to T and stored as the
+// GEMM's output; the LayerNorm of those rounded values follows in the same registers.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void splitk_layernorm_fwd_kernel(const float* __restrict__ planes, int slices,
+                                                                        size_t plane, const float* __restrict__ bias,
+                                                                        const T* __restrict__ resid,
+                                                                        T* __restrict__ y, const float* __restrict__ gamma,
+                                                                        const float* __restrict__ beta,
+                                                                        T* __restrict__ out, float* __restrict__ stats,
+                                                                        int h, float eps) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const size_t off = row * h;
+  float v[kMaxChunks][kVec];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      float acc[4], b[4], r[4];
+      Vec4<float>::load(planes + off + col, acc);
+      for (int sl = 1; sl < slices; ++sl) {
+        float p[4];
+        Vec4<float>::load(planes + (size_t)sl * plane + off + col, p);
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) acc[e] += p[e];
+      }
+      Vec4<float>::load(bias + col, b);
+      Vec4<T>::load(resid + off + col, r);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) v[c][e] = to_f32(from_f32<T>(acc[e] + b[e] + r[e]));
+      Vec4<T>::store(y + off + col, v[c]);
+      sum += (v[c][0] + v[c][1]) + (v[c][2] + v[c][3]);
+    }
+  }
+  const float mean = block_sum(sum, red) / (float)h;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) {
+        const float d = v[c][e] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float var = block_sum(sq, red) / (float)h;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  if (threadIdx.x == 0) {
+    stats[row * 2] = mean;
+    stats[row * 2 + 1] = rstd;
+  }
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      float g[4], b[4], o[4];
+      Vec4<float>::load(gamma + col, g);
+      Vec4<float>::load(beta + col, b);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) o[e] = (v[c][e] - mean) * rstd * g[e] + b[e];
+      Vec4<T>::store(out + off + col, o);
+    }
+  }
+}
+
 // sums of two values over the 256 threads of a workgroup with one exchange
 __device__ __forceinline__ void block_sum2(float& a, float& b, float (*red)[2]) {
   a = wave_sum(a);
@@ -204,6 +273,65 @@ __device__ __forceinline__ void layernorm_bwd_param_body(int bx, int by, const T
   }
 }
 
+// LayerNorm backward fused with the end of the split-K dgrad GEMM that produces its incoming gradient g: one
+// row per workgroup; g = the sum of the `slices` planes (slice order), rounded to T and stored (the gamma /
+// beta sums read it afterwards); dx as in layernorm_bwd_dx_body, from the same registers.
+template <typename T, int NCH>
+__global__ __launch_bounds__(kThreads) void splitk_layernorm_bwd_kernel(const float* __restrict__ planes, int slices,
+                                                                        size_t plane, T* __restrict__ g_out,
+                                                                        const T* __restrict__ x,
+                                                                        const float* __restrict__ stats,
+                                                                        const float* __restrict__ gamma,
+                                                                        const T* __restrict__ resid, T* __restrict__ dx,
+                                                                        int h) {
+  __shared__ float red[4][2];
+  const int row = blockIdx.x;
+  const size_t off = (size_t)row * h;
+  const float mean = stats[row * 2], rstd = stats[row * 2 + 1];
+  float gg[NCH][kVec], xh[NCH][kVec], rr[NCH][kVec];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      float acc[4], gam[kVec];
+      Vec4<float>::load(planes + off + col, acc);
+      for (int sl = 1; sl < slices; ++sl) {
+        float p[4];
+        Vec4<float>::load(planes + (size_t)sl * plane + off + col, p);
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) acc[e] += p[e];
+      }
+      Vec4<T>::load(x + off + col, xh[c]);
+      if (resid) Vec4<T>::load(resid + off + col, rr[c]);
+      else rr[c][0] = rr[c][1] = rr[c][2] = rr[c][3] = 0.f;
+      Vec4<float>::load(gamma + col, gam);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) gg[c][e] = to_f32(from_f32<T>(acc[e]));
+      Vec4<T>::store(g_out + off + col, gg[c]);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) {
+        xh[c][e] = (xh[c][e] - mean) * rstd;
+        gg[c][e] *= gam[e];
+        s1 += gg[c][e];
+        s2 += gg[c][e] * xh[c][e];
+      }
+    }
+  }
+  block_sum2(s1, s2, red);
+  const float m1 = s1 / (float)h, m2 = s2 / (float)h;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (c * kThreads + threadIdx.x) * kVec;
+    if (col < h) {
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) o[e] = rr[c][e] + rstd * (gg[c][e] - m1 - xh[c][e] * m2);
+      Vec4<T>::store(dx + off + col, o);
+    }
+  }
+}
+
 // One launch for both: workgroups 0 .. rows-1 compute dx of one row each, the rest the gamma / beta partial
 // sums (column block bx, row slice by).  Nothing downstream waits for the partial sums, so they ride along
 // with the dx rows instead of taking a launch of their own.
@@ -213,11 +341,11 @@ __global__ __launch_bounds__(kThreads) void layernorm_bwd_kernel(const T* __rest
                                                                  const float* __restrict__ gamma,
                                                                  const T* __restrict__ resid, T* __restrict__ dx,
                                                                  float* __restrict__ partials, int rows, int h,
-                                                                 int rows_per_slice, int col_blocks) {
-  if ((int)blockIdx.x < rows) {
+                                                                 int rows_per_slice, int col_blocks, int dx_rows) {
+  if ((int)blockIdx.x < dx_rows) {
     layernorm_bwd_dx_body<T, NCH>(blockIdx.x, g, x, stats, gamma, resid, dx, h);
   } else {
-    const int q = blockIdx.x - rows;
+    const int q = blockIdx.x - dx_rows;
     layernorm_bwd_param_body<T>(q % col_blocks, q / col_blocks, g, x, stats, partials, rows, h, rows_per_slice);
   }
 }
@@ -398,7 +526,7 @@ hipError_t run_ln_bwd(const T* g, const T* x, const float* stats, const float* g
                       float* partials, int rows, int h, int slices, hipStream_t s) {
   const int rows_per_slice = (rows + slices - 1) / slices, col_blocks = (h + 127) / 128;
   layernorm_bwd_kernel<T, NCH><<<rows + col_blocks * slices, kThreads, 0, s>>>(g, x, stats, gamma, resid, dx, partials,
-                                                                             rows, h, rows_per_slice, col_blocks);
+                                                                             rows, h, rows_per_slice, col_blocks, rows);
   return hipGetLastError();
 }
 
@@ -423,6 +551,46 @@ hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, cons
   }
   if (e != hipSuccess) return e;
   layernorm_bwd_reduce_kernel<<<(h + 63) / 64, 256, 0, s>>>(partials, dgamma, dbeta, slices, h);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_splitk_layernorm_fwd(const float* planes, int slices, size_t plane, const float* bias, const T* resid,
+                                       T* y, const float* gamma, const float* beta, T* out, float* stats, int rows,
+                                       int h, float eps, hipStream_t s) {
+  if (h % kVec != 0 || h > kThreads * kVec * kMaxChunks || rows <= 0 || slices < 1) return hipErrorInvalidValue;
+  splitk_layernorm_fwd_kernel<T><<<rows, kThreads, 0, s>>>(planes, slices, plane, bias, resid, y, gamma, beta, out, stats,
+                                                          h, eps);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_splitk_layernorm_bwd(const float* planes, int slices, size_t plane, T* g_out, const T* x,
+                                       const float* stats, const float* gamma, const T* resid, T* dx, float* dgamma,
+                                       float* dbeta, float* partials, int rows, int h, hipStream_t s) {
+  if (h % kVec != 0 || h > kThreads * kVec * kMaxChunks || rows <= 0 || slices < 1) return hipErrorInvalidValue;
+  const int nch = (h + kThreads * kVec - 1) / (kThreads * kVec);
+  int pslices = (rows + 15) / 16;
+  if (pslices > kLnBwdSlices) pslices = kLnBwdSlices;
+  const int rows_per_slice = (rows + pslices - 1) / pslices, col_blocks = (h + 127) / 128;
+#define ZB_RUN(N)                                                                                                   \
+  splitk_layernorm_bwd_kernel<T, N><<<rows, kThreads, 0, s>>>(planes, slices, plane, g_out, x, stats, gamma, resid,  \
+                                                              dx, h);                                               \
+  layernorm_bwd_kernel<T, N><<<col_blocks * pslices, kThreads, 0, s>>>(g_out, x, stats, gamma, resid, dx, partials,  \
+                                                                       rows, h, rows_per_slice, col_blocks, 0)
+  switch (nch) {
+    case 1: ZB_RUN(1); break;
+    case 2: ZB_RUN(2); break;
+    case 3: ZB_RUN(3); break;
+    case 4: ZB_RUN(4); break;
+    case 5: ZB_RUN(5); break;
+    case 6: ZB_RUN(6); break;
+    default: ZB_RUN(8); break;
+  }
+#undef ZB_RUN
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  layernorm_bwd_reduce_kernel<<<(h + 63) / 64, 256, 0, s>>>(partials, dgamma, dbeta, pslices, h);
   return hipGetLastError();
 }
 
@@ -512,6 +680,12 @@ template <typename T> hipError_t launch_poke(T* dst, size_t idx, float v, hipStr
                                               float*, float*, float*, int, int, hipStream_t);                    \
   template hipError_t launch_colsum_accum_multi<T>(const void* const*, float* const*, const int*, int, float*,  \
                                                    int, hipStream_t);                                           \
+  template hipError_t launch_splitk_layernorm_fwd<T>(const float*, int, size_t, const float*, const T*, T*,      \
+                                                     const float*, const float*, T*, float*, int, int, float,    \
+                                                     hipStream_t);                                               \
+  template hipError_t launch_splitk_layernorm_bwd<T>(const float*, int, size_t, T*, const T*, const float*,      \
+                                                     const float*, const T*, T*, float*, float*, float*, int,    \
+                                                     int, hipStream_t);                                          \
   template hipError_t launch_convert_from_f32<T>(const float*, T*, size_t, hipStream_t);                         \
   template hipError_t launch_convert_to_f32<T>(const T*, float*, size_t, hipStream_t);                           \
   template hipError_t launch_gather_columns<T>(const T*, long, int, const int*, int, float*, hipStream_t);        \

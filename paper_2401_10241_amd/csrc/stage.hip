@@ -401,6 +401,7 @@ template <typename T> struct Exec {
                                          (T*)(st->in_x + st->act_bytes * (size_t)mb), T_, h, st->s, s));
       ZB_HIP(st, launch_sort_tokens(ids, st->perm + (size_t)mb * T_, T_, s));  // for the table's gradient in W
     }
+    bool ln1_done = false;  // LayerNorm 1 of the layer already written by the previous layer's last GEMM
     for (int l = l_lo; l <= l_hi; ++l) {
       const LayerOff& q = st->lo[l];
       T* A = (T*)(fw + q.fw_a);
@@ -414,7 +415,7 @@ template <typename T> struct Exec {
       float* st2 = (float*)(fb + q.fb_stats2);
       float* lse = (float*)(fb + q.fb_lse);
       T* y = (l == l_hi) ? (T*)(st->out_y + st->act_bytes * (size_t)mb) : (T*)(fb + st->lo[l + 1].fb_x);
-      {
+      if (!ln1_done) {
         ProfScope ps(st, KC_LN_FWD, 0, 2 * E * T_ * h + 8.0 * T_);
         ZB_HIP(st, launch_layernorm_fwd<T>(x, st->P(l, ZB_P_LN1_G), st->P(l, ZB_P_LN1_B), A, st1, T_, h,
                                             st->cfg.ln_eps, s));
@@ -434,8 +435,11 @@ template <typename T> struct Exec {
       g.A = C; g.B = st->Wt(l, ZB_P_WO); g.M = T_; g.N = h; g.K = h;
       g.a_sm = h; g.a_sk = 1; g.b_sk = h; g.b_sn = 1;
       g.epilogue = EPI_BIAS_RESID; g.out0 = Y1; g.bias = st->P(l, ZB_P_BO); g.aux = x;
+      bool ln2_done = false;  // LayerNorm 2 rides along with the projection GEMM where that runs as K slices
+      g.ln_mode = 1; g.ln_gamma = st->P(l, ZB_P_LN2_G); g.ln_beta = st->P(l, ZB_P_LN2_B); g.ln_out = U;
+      g.ln_stats = st2; g.ln_eps = st->cfg.ln_eps; g.ln_done = &ln2_done;
       ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
-      {
+      if (!ln2_done) {
         ProfScope ps(st, KC_LN_FWD, 0, 2 * E * T_ * h + 8.0 * T_);
         ZB_HIP(st, launch_layernorm_fwd<T>(Y1, st->P(l, ZB_P_LN2_G), st->P(l, ZB_P_LN2_B), U, st2, T_, h,
                                             st->cfg.ln_eps, s));
@@ -449,6 +453,13 @@ template <typename T> struct Exec {
       g.A = Gl; g.B = st->Wt(l, ZB_P_W2); g.M = T_; g.N = h; g.K = f;
       g.a_sm = f; g.a_sk = 1; g.b_sk = h; g.b_sn = 1;
       g.epilogue = EPI_BIAS_RESID; g.out0 = y; g.bias = st->P(l, ZB_P_B2); g.aux = Y1;
+      ln1_done = false;
+      if (l < l_hi) {  // the next layer's LayerNorm 1 on the rows this GEMM finishes
+        const LayerOff& qn = st->lo[l + 1];
+        g.ln_mode = 1; g.ln_gamma = st->P(l + 1, ZB_P_LN1_G); g.ln_beta = st->P(l + 1, ZB_P_LN1_B);
+        g.ln_out = fw + qn.fw_a; g.ln_stats = (float*)(fb + qn.fb_stats1); g.ln_eps = st->cfg.ln_eps;
+        g.ln_done = &ln1_done;
+      }
       ZB_HIP(st, gemm(st, KC_GEMM_FWD, g));
       x = y;
     }
@@ -571,8 +582,12 @@ template <typename T> struct Exec {
       g.A = dFh; g.M = T_; g.N = h; g.K = f;
       g.a_sm = f; g.a_sk = 1; dgrad_weight(st, &g, l, ZB_P_W1, h, f);
       g.epilogue = EPI_STORE; g.out0 = tmp;
+      bool lnb_done = false;  // LayerNorm 2's backward on the rows this GEMM finishes (K slices only)
+      g.ln_mode = 2; g.ln_x = Y1; g.ln_stats = const_cast<float*>(st2); g.ln_gamma = st->P(l, ZB_P_LN2_G);
+      g.ln_resid = dy; g.ln_out = dY1; g.ln_dgamma = st->G(l, ZB_P_LN2_G); g.ln_dbeta = st->G(l, ZB_P_LN2_B);
+      g.ln_partials = st->ln_partials; g.ln_done = &lnb_done;
       ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
-      {
+      if (!lnb_done) {
         ProfScope ps(st, KC_LN_BWD, 0, 4 * E * T_ * h);
         ZB_HIP(st, launch_layernorm_bwd<T>(tmp, Y1, st2, st->P(l, ZB_P_LN2_G), dy, dY1, st->G(l, ZB_P_LN2_G),
                                             st->G(l, ZB_P_LN2_B), st->ln_partials, T_, h, s));
@@ -593,8 +608,12 @@ template <typename T> struct Exec {
       g.A = dQKV; g.M = T_; g.N = h; g.K = 3 * h;
       g.a_sm = 3 * h; g.a_sk = 1; dgrad_weight(st, &g, l, ZB_P_WQKV, h, 3 * h);
       g.epilogue = EPI_STORE; g.out0 = tmp;
+      lnb_done = false;  // LayerNorm 1's backward likewise
+      g.ln_mode = 2; g.ln_x = xl; g.ln_stats = const_cast<float*>(st1); g.ln_gamma = st->P(l, ZB_P_LN1_G);
+      g.ln_resid = dY1; g.ln_out = dx; g.ln_dgamma = st->G(l, ZB_P_LN1_G); g.ln_dbeta = st->G(l, ZB_P_LN1_B);
+      g.ln_partials = st->ln_partials; g.ln_done = &lnb_done;
       ZB_HIP(st, gemm(st, KC_GEMM_DGRAD, g));
-      {
+      if (!lnb_done) {
         ProfScope ps(st, KC_LN_BWD, 0, 4 * E * T_ * h);
         ZB_HIP(st, launch_layernorm_bwd<T>(tmp, xl, st1, st->P(l, ZB_P_LN1_G), dY1, dx, st->G(l, ZB_P_LN1_G),
                                             st->G(l, ZB_P_LN1_B), st->ln_partials, T_, h, s));

@@ -80,6 +80,19 @@ struct GemmArgs {
   int group;
   const void* group_a[16];
   const void* group_b[16];
+  // Optional LayerNorm on the rows of the output (N = the LayerNorm width), taken only when the GEMM runs as K
+  // slices, whose last step owns whole rows; *ln_done tells the caller (false: it runs the LayerNorm itself).
+  //   ln_mode 1 (with EPI_BIAS_RESID): forward, ln_out = LayerNorm(out0; ln_gamma, ln_beta), ln_stats written
+  //   ln_mode 2 (with EPI_STORE): backward of the LayerNorm whose output gradient this GEMM computes:
+  //     ln_out = ln_resid + LNbwd(out0; ln_x, ln_stats, ln_gamma), ln_dgamma / ln_dbeta += ...
+  int ln_mode;
+  const float *ln_gamma, *ln_beta;
+  float* ln_stats;
+  void* ln_out;
+  float ln_eps;
+  const void *ln_x, *ln_resid;
+  float *ln_dgamma, *ln_dbeta, *ln_partials;
+  bool* ln_done;
 };
 constexpr int kGemmGroupMax = 16;
 
@@ -127,6 +140,20 @@ hipError_t launch_layernorm_bwd(const T* g, const T* x, const float* stats, cons
                                 T* dx, float* dgamma, float* dbeta, float* partials, int rows, int h,
                                 hipStream_t s);
 constexpr int kLnBwdSlices = 16;
+
+// The same two LayerNorm passes fused with the end of a split-K GEMM (`slices` dense fp32 planes of [rows, h],
+// `plane` floats apart, added in slice order):
+//   forward:  y = T(sum of planes + bias + resid) is the GEMM's output; out = LayerNorm(y), stats as above
+//   backward: g = T(sum of planes) is the dgrad GEMM's output (stored to g_out); dx = resid + LNbwd(g);
+//             partials as for launch_layernorm_bwd
+template <typename T>
+hipError_t launch_splitk_layernorm_fwd(const float* planes, int slices, size_t plane, const float* bias, const T* resid,
+                                       T* y, const float* gamma, const float* beta, T* out, float* stats, int rows,
+                                       int h, float eps, hipStream_t s);
+template <typename T>
+hipError_t launch_splitk_layernorm_bwd(const float* planes, int slices, size_t plane, T* g_out, const T* x,
+                                       const float* stats, const float* gamma, const T* resid, T* dx, float* dgamma,
+                                       float* dbeta, float* partials, int rows, int h, hipStream_t s);
 
 // bias gradients: db[q][c] += sum_rows dy[q][r, c] for `count` <= 4 matrices dy[q] of [rows, n[q]] in one launch
 // pair; row slices are added in a fixed order; scratch holds kColsumSlices * (n[0] + ... + n[count-1]) floats
