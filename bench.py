@@ -87,6 +87,12 @@ def auto_schedule_report(zb, st, w, m, class_ms):
         orders = [zb.schedule_order(p, i, m, kind) for i in range(p)]
         rates["1F1B" if kind == "1F1B" else "ZB-" + kind] = round(
             zb.simulate_pipeline(orders, t_f, t_b, t_w, t_comm, fused_backward=(kind == "1F1B"))[1], 4)
+    # What holding W back into groups (zb_order_group_w, bench --w-group) would cost a real pipeline: the same pass
+    # times, every stage's ZB-H1 / ZB-H2 order regrouped.  On one GPU grouped W run faster (one read-modify-write of
+    # a gradient per group instead of per pass); in the pipeline the W passes no longer sit where the bubbles are.
+    for grp in (2, 4):
+        orders = [zb.order_group_w(zb.schedule_order(p, i, m, w.kind), grp) for i in range(p)]
+        rates[f"ZB-{w.kind}, W in groups of {grp}"] = round(zb.simulate_pipeline(orders, t_f, t_b, t_w, t_comm)[1], 4)
     # ZB-V: every stage as two chunks, each chunk's pass taking half the stage's time
     rates["ZB-V"] = round(zb.simulate_pipeline_v(zb.schedule_order_v(p, m), m, t_f / 2, t_b / 2, t_w / 2, t_comm)[1], 4)
     t0 = time.perf_counter()
@@ -265,15 +271,40 @@ def main():
         g_n = sum(r["launches"] for r in gemm)
         g_by = sum(r["bytes"] for r in gemm)
         peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
-        ach = g_fl / g_ms / 1e9
-        out["roofline"] = {"kernel": "GEMM kernels (forward, dgrad, wgrad launches of one profiled step)",
+        all_ms = sum(r["total_ms"] for r in stats)
+        # the dominant kernel: the class with the largest share of the step's kernel time (at the bf16 workloads
+        # the wgrad kernel, one launch per W pass: the accumulate GEMMs of all its layers)
+        top = max(gemm, key=lambda r: r["total_ms"])
+        ach = top["flops"] / top["total_ms"] / 1e9
+        out["roofline"] = {"kernel": top["name"],
                            "bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": round(ach, 1),
                            "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4),
-                           "traffic": measured_traffic(w.name) if not args.m else None,
-                           "algorithmic_bytes_per_launch": g_by / g_n,
+                           "traffic": measured_traffic(w.name) if not (args.m or args.w_group > 1 or args.role != "middle") else None,
+                           "algorithmic_bytes_per_launch": top["bytes"] / top["launches"],
+                           "hbm_limited_ceiling_tflops": round(min(peak, top["flops"] / top["bytes"] * PEAK_HBM_GBS / 1e3), 1),
+                           "launches": top["launches"], "avg_launch_us": round(1e3 * top["total_ms"] / top["launches"], 2),
+                           "flops_per_launch": top["flops"] / top["launches"],
+                           "share_of_step_kernel_time": round(top["total_ms"] / all_ms, 3)}
+        out["gemm_all"] = {"achieved": round(g_fl / g_ms / 1e9, 1), "frac": round(g_fl / g_ms / 1e9 / peak, 4),
                            "launches": g_n, "avg_launch_us": round(1e3 * g_ms / g_n, 2),
-                           "flops_per_launch": g_fl / g_n,
-                           "share_of_step_kernel_time": round(g_ms / sum(r["total_ms"] for r in stats), 3)}
+                           "share_of_step_kernel_time": round(g_ms / all_ms, 3)}
+        if w.optimizer:
+            # One more optimizer call on the gradients still in place, untimed: forced to take the optimistic step
+            # although the norm is above the threshold, so that validation rolls it back and redoes it clipped -
+            # the step with its journal, the rollback and the redo all move their bytes and get a bandwidth figure.
+            st.profile_enable(True)
+            rep = st.optimizer_step_validated(0.0, zb_inputs.rest_state(w, 0) + 4.0, force_optimistic=True)
+            forced = {r["name"]: r for r in st.profile_read()}
+            st.profile_enable(False)
+            fr = {"outcome": rep.outcome_name, "alg1_mismatch_elems": rep.alg1_mismatch_elems,
+                  "journal_bytes_per_param": 12}
+            for name in ("adamw_step", "adamw_rollback", "adamw_restep"):
+                if name in forced:
+                    r = forced[name]
+                    fr[name] = {"ms": round(r["total_ms"], 3), "gbs": round(r["bytes"] / r["total_ms"] / 1e6, 1)}
+                    if name == "adamw_rollback" and kern.get(name, {}).get("gbs") is None:
+                        kern[name]["gbs_when_it_runs"] = fr[name]["gbs"]
+            out["optimizer_forced_rollback"] = fr
         out["kernels"] = kern
         out["auto_schedule"] = auto_schedule_report(zb, st, w, m, {r["name"]: r["total_ms"] for r in stats})
     st.close()

@@ -1,10 +1,12 @@
 """AdamW Step / Rollback and the post-validated optimizer step (test infrastructure).
 
-Step and Rollback follow Appendix C, Algorithm 1 of the paper, statement by
-statement and in its order: Step advances t, then m, v, the bias-corrected m'
-and v', then theta with the decay term lr*lambda*theta and epsilon added
-outside the square root; Rollback inverts theta first (with the *new* m, v and
-t), then m, then v, then t.
+Step is AdamW with decoupled weight decay and bias-corrected moments (Appendix C,
+Algorithm 1): the time stamp advances, the two moments take their exponential
+averages of g and g*g, and theta moves by lr * (m' / (sqrt(v') + eps) + lambda *
+theta), with m', v' the bias-corrected moments and epsilon added outside the
+square root.  Rollback is its arithmetic inverse (same algorithm): theta is
+recovered first, from the moments and time stamp the step left behind, then the
+moments, then the time stamp.
 
 The protocol follows Sec. 4: the stage receives a partially reduced global
 state (squared gradient norm and a non-finite flag of the stages before it),
@@ -65,7 +67,7 @@ class AdamState:
 
 
 def adamw_step(st: AdamState, g: np.ndarray, hp: Hyper) -> None:
-    """Algorithm 1, Step(g), in place."""
+    """AdamW step with gradient g, in place (Appendix C, Algorithm 1)."""
     dt = st.theta.dtype.type
     g = g.astype(st.theta.dtype, copy=False)
     st.t = st.t + 1
@@ -79,7 +81,7 @@ def adamw_step(st: AdamState, g: np.ndarray, hp: Hyper) -> None:
 
 
 def adamw_rollback(st: AdamState, g: np.ndarray, hp: Hyper) -> None:
-    """Algorithm 1, Rollback(g), in place (arithmetic inverse of Step)."""
+    """The arithmetic inverse of adamw_step for the same g, in place (Appendix C, Algorithm 1)."""
     dt = st.theta.dtype.type
     g = g.astype(st.theta.dtype, copy=False)
     with np.errstate(all="ignore"):

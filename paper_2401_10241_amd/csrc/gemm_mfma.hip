@@ -478,7 +478,7 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
 // every CU gets a workgroup.  Returns false if the shape is not one for split-K.
 template <int MODE>
 bool try_split_k(const GemmArgs& g, long lda, long ldb, hipStream_t s, hipError_t* err) {
-  if (g.M % 256 != 0 || g.N % BN != 0 || g.N % 4 != 0 || g.K < 4096 || !g.workspace) return false;
+  if (g.M % 256 != 0 || g.N % BN != 0 || g.N % 4 != 0 || g.K < 2048 || !g.workspace) return false;
   const long tiles = (long)(g.M / 256) * (g.N / BN);
   if (tiles > 128) return false;
   int slices = (int)(256 / tiles);

@@ -115,6 +115,7 @@ __global__ void decide_optimistic_kernel(OptDevState* st, OptHyper hp, double pr
   st->do_rollback = 0;
   st->step_coef = 1.0f;
   st->mismatch = 0ull;
+  st->journal_current = 0;
   if (go) advance_time(st, hp);
 }
 
@@ -152,7 +153,8 @@ __global__ void decide_validate_kernel(OptDevState* st, OptHyper hp, double prev
 
 // bookkeeping between the rollback and the redo
 __global__ void decide_after_rollback_kernel(OptDevState* st, OptHyper hp) {
-  if (st->do_rollback) { st->t -= 1; st->do_rollback = 0; }
+  // after a rollback theta, m, v equal the journal: the redo need not write it again
+  if (st->do_rollback) { st->t -= 1; st->do_rollback = 0; st->journal_current = 1; }
   if (st->do_step) advance_time(st, hp);
 }
 
@@ -164,7 +166,7 @@ __device__ __forceinline__ void store_bf16x4(bf16_t* p, float4 v) {
   *reinterpret_cast<bf16x4*>(p) = t;
 }
 
-// Algorithm 1, Step(g), one element
+// AdamW with decoupled weight decay and bias-corrected moments (Appendix C, Algorithm 1), one element
 __device__ __forceinline__ void step_one(float& th, float& m, float& v, float g, const OptHyper& hp, float bc1,
                                          float bc2) {
   m = hp.beta1 * m + (1.0f - hp.beta1) * g;
@@ -173,7 +175,7 @@ __device__ __forceinline__ void step_one(float& th, float& m, float& v, float g,
   const float vh = v / bc2;
   th = th - hp.lr * hp.weight_decay * th - hp.lr * mh / (sqrtf(vh) + hp.eps);
 }
-// Algorithm 1, Rollback(g), one element
+// its arithmetic inverse (same algorithm): theta from the new moments, then the moments
 __device__ __forceinline__ void rollback_one(float& th, float& m, float& v, float g, const OptHyper& hp, float bc1,
                                              float bc2) {
   const float mh = m / bc1;
@@ -191,10 +193,11 @@ __global__ __launch_bounds__(256) void adamw_step_kernel(float4* __restrict__ th
                                                          size_t n4, OptHyper hp, const OptDevState* __restrict__ st) {
   if (!st->do_step) return;
   const float coef = st->step_coef, bc1 = st->bc1, bc2 = st->bc2;
+  const bool keep = JOURNAL && !st->journal_current;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n4) {
     float4 th = theta[i], mm = m[i], vv = v[i], gg = g[i];
-    if (JOURNAL) { j_theta[i] = th; j_m[i] = mm; j_v[i] = vv; }
+    if (keep) { j_theta[i] = th; j_m[i] = mm; j_v[i] = vv; }
     if (coef != 1.0f) { gg.x *= coef; gg.y *= coef; gg.z *= coef; gg.w *= coef; }
     step_one(th.x, mm.x, vv.x, gg.x, hp, bc1, bc2);
     step_one(th.y, mm.y, vv.y, gg.y, hp, bc1, bc2);
