@@ -401,7 +401,7 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
     for (int j = 0; j < NT; ++j) {
       const float* p0 = outf + (size_t)(m0 + wm + i * 32 + lhi) * N + n0 + wn + j * 32 + lrow;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = p0[(size_t)((v >> 2) * 8 + (v & 3)) * N];
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = __builtin_nontemporal_load(p0 + (size_t)((v >> 2) * 8 + (v & 3)) * N);
       __builtin_amdgcn_sched_barrier(0);  // one tile's addresses at a time
     }
 
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
     for (int j = 0; j < NT; ++j) {
       float* p0 = outf + (size_t)(m0s + wm + i * 32 + lhi) * N + n0s + wn + j * 32 + lrow;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) p0[(size_t)((v >> 2) * 8 + (v & 3)) * N] = acc[i][j][v];
+      for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(acc[i][j][v], p0 + (size_t)((v >> 2) * 8 + (v & 3)) * N);
       __builtin_amdgcn_sched_barrier(0);
     }
 }
