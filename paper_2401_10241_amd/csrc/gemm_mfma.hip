@@ -359,7 +359,50 @@ struct WgradTable {
   float* outf[kWgradMaxProblems];
   const bf16_t* a[kWgradMaxPairs];   // pair g of problem q at [q * ngroup + g]
   const bf16_t* b[kWgradMaxPairs];
+  int ntiles;                        // workgroups [0, ntiles) are GEMM tiles, the rest column-sum strips
+  int strip0[kWgradMaxProblems + 1]; // first strip (256 columns) of each problem; equal entries: no bias
+  float* bias[kWgradMaxProblems];
 };
+
+// Bias gradient of one 256-column strip of one problem: bias[n] += sum over the Kc rows of every operand pair's
+// b (the output gradient), pair by pair.  512 threads = 32 chunks of 8 columns x 16 row groups; a thread adds
+// its rows in ascending order, the 16 row groups are added in ascending order, then the pair's sum goes onto
+// the running value: the same chain of additions whether the pairs come in one launch or one launch each.
+__device__ __forceinline__ void wgrad_bias_strip(const WgradTable& tb, int sid, int Kc, float* red) {
+  int q = 0;
+#pragma unroll
+  for (int i = 1; i < kWgradMaxProblems; ++i) q += (i < tb.nprob && sid >= tb.strip0[i]) ? 1 : 0;
+  sid -= tb.strip0[q];
+  const int N = tb.N[q], ngroup = tb.ngroup;
+  const int n0 = sid * BN;
+  const int c = threadIdx.x & 31, g = threadIdx.x >> 5;
+  float* __restrict__ bias = tb.bias[q];
+  float run = 0.f;
+  if (threadIdx.x < BN) run = bias[n0 + threadIdx.x];
+  for (int gi = 0; gi < ngroup; ++gi) {
+    const bf16_t* __restrict__ b = tb.b[q * ngroup + gi] + n0 + c * 8;
+    float sum[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum[j] = 0.f;
+#pragma unroll 8
+    for (int r = g; r < Kc; r += 16) {
+      const bf16x8 v = *reinterpret_cast<const bf16x8*>(b + (long)r * N);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum[j] += (float)v[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[g * BN + c * 8 + j] = sum[j];
+    __syncthreads();
+    if (threadIdx.x < BN) {
+      float t = 0.f;
+#pragma unroll
+      for (int gg = 0; gg < 16; ++gg) t += red[gg * BN + threadIdx.x];
+      run += t;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x < BN) bias[n0 + threadIdx.x] = run;
+}
 
 template <int BM, int BS, bool XB>
 __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgrad_kernel(WgradTable tb, int Kc) {
@@ -370,8 +413,12 @@ __global__ __launch_bounds__(512, (BM == 128 && BS == 3) ? 4 : 2) void gemm_wgra
   constexpr int WM = BM / 2;
   constexpr int MT = WM / 32, NT = WN / 32;
 
-  const int nblk = gridDim.x;
+  const int nblk = tb.ntiles;
   int pid = blockIdx.x;
+  if (pid >= nblk) {  // the launch's last workgroups: bias gradients (they fill the CUs the last round of tiles leaves idle)
+    wgrad_bias_strip(tb, pid - nblk, Kc, reinterpret_cast<float*>(smem_raw));
+    return;
+  }
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
   int q = 0;  // which problem this tile belongs to
 #pragma unroll
@@ -606,7 +653,15 @@ hipError_t run_wgrad(WgradTable& tb, int K, hipStream_t s) {
     tiles += (tb.M[q] / BM) * (tb.N[q] / BN);
   }
   for (int q = tb.nprob; q <= kWgradMaxProblems; ++q) tb.tile0[q] = tiles;
-  kern<<<tiles, NTHREADS, smem, s>>>(tb, K);
+  tb.ntiles = tiles;
+  int strips = 0;
+  for (int q = 0; q < tb.nprob; ++q) {
+    tb.strip0[q] = strips;
+    if (tb.bias[q]) strips += tb.N[q] / BN;
+  }
+  for (int q = tb.nprob; q <= kWgradMaxProblems; ++q) tb.strip0[q] = strips;
+  static_assert(smem >= 16 * BN * sizeof(float), "the strips' reduction buffer");
+  kern<<<tiles + strips, NTHREADS, smem, s>>>(tb, K);
   return hipGetLastError();
 }
 
@@ -636,6 +691,7 @@ template <> hipError_t launch_wgrad_multi_mfma<bf16_t>(const WgradMultiArgs& w, 
     const int M = w.M[q], N = w.N[q];
     if (M <= 0 || N <= 0 || M % 128 != 0 || N % BN != 0 || !aligned16(w.outf[q])) return hipSuccess;
     tb.M[q] = M; tb.N[q] = N; tb.outf[q] = w.outf[q];
+    tb.bias[q] = w.bias_done ? w.bias[q] : nullptr;
     all256 = all256 && M % 256 == 0;
     t256 += (long)(M / 256) * (N / BN);
     t128 += (long)(M / 128) * (N / BN);
@@ -649,6 +705,7 @@ template <> hipError_t launch_wgrad_multi_mfma<bf16_t>(const WgradMultiArgs& w, 
   }
   if (t128 >= (1L << 30)) return hipSuccess;
   *taken = true;
+  if (w.bias_done) *w.bias_done = true;
   // 256-row tiles (one workgroup per CU, four-stage ring) when they fill most of the chip; else 128-row
   // tiles, two workgroups per CU with a three-stage ring if there are more tiles than CUs, one with a
   // five-stage ring otherwise.  The choice does not change the result (see the kernel).

@@ -625,8 +625,9 @@ template <typename T> struct Exec {
   // W of n microbatches (1 <= n <= kGemmGroupMax, all of one chunk) for layers l_hi .. l_lo: the accumulate
   // GEMMs of as many whole layers as one launch takes (tiles of equal duration, so the partly filled last
   // round of workgroups is paid once per launch, not once per weight matrix), each summing its n operand
-  // pairs in the order given; then the bias column sums, layer by layer and microbatch by microbatch in the
-  // same order.
+  // pairs in the order given.  The bias gradients (column sums of the same dY operands, microbatch by
+  // microbatch in the same order) are taken by extra workgroups of that launch where the MFMA kernel runs it,
+  // by the column-sum kernels otherwise.
   static zb_status wgrad_layers(zb_stage* st, const int* mbs, int n, int l_hi, int l_lo) {
     const int h = st->h, f = st->ffn, T_ = st->T;
     hipStream_t s = st->stream;
@@ -648,17 +649,19 @@ template <typename T> struct Exec {
     int per_launch = kWgradMaxPairs / (4 * n);  // whole layers per launch
     if (per_launch > kWgradMaxProblems / 4) per_launch = kWgradMaxProblems / 4;
     if (per_launch < 1) per_launch = 1;
+    std::vector<char> bias_in_launch(st->L, 0);
     for (int l1 = l_hi; l1 >= l_lo; l1 -= per_launch) {
       const int l0 = l1 - per_launch + 1 > l_lo ? l1 - per_launch + 1 : l_lo;
       WgradMultiArgs w{};
-      w.ngroup = n; w.K = T_;
+      bool bias_done = false;
+      w.ngroup = n; w.K = T_; w.bias_done = &bias_done;
       double flops = 0, bytes = 0;
       for (int l = l1; l >= l0; --l) {
         Lin lins[4];
         lins_of(l, lins);
         for (const Lin& ln : lins) {
           const int q = w.nprob++;
-          w.M[q] = ln.kin; w.N[q] = ln.nout; w.outf[q] = st->G(l, ln.wi);
+          w.M[q] = ln.kin; w.N[q] = ln.nout; w.outf[q] = st->G(l, ln.wi); w.bias[q] = st->G(l, ln.bi);
           for (int i = 0; i < n; ++i) {
             const char* fw = st->fw_pool + st->fw_slot * (size_t)st->slot_fw[mbs[i]];
             w.a[q * n + i] = fw + ln.fw_off;
@@ -672,8 +675,11 @@ template <typename T> struct Exec {
         ProfScope ps(st, KC_GEMM_WGRAD, flops, bytes);
         ZB_HIP(st, launch_wgrad_multi<T>(w, s));
       }
+      if (bias_done)
+        for (int l = l1; l >= l0; --l) bias_in_launch[l] = 1;
     }
     for (int l = l_hi; l >= l_lo; --l) {
+      if (bias_in_launch[l]) continue;  // the wgrad launch summed the columns of its dY operands itself
       Lin lins[4];
       lins_of(l, lins);
       for (int i = 0; i < n; ++i) {  // the four bias gradients: column sums of the same dY's

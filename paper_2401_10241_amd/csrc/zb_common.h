@@ -108,6 +108,10 @@ struct WgradMultiArgs {
   float* outf[kWgradMaxProblems];
   const void* a[kWgradMaxPairs];  // pair g of problem q at [q * ngroup + g]
   const void* b[kWgradMaxPairs];
+  // optional: bias[q] (N[q] floats) += column sums of problem q's b operands, pair by pair in the order given.
+  // *bias_done is set if the launch did it (extra workgroups of the same launch); otherwise the caller does.
+  float* bias[kWgradMaxProblems];
+  bool* bias_done;
 };
 template <typename T> hipError_t launch_wgrad_multi(const WgradMultiArgs& w, hipStream_t s);
 
