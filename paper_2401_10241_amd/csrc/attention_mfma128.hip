@@ -21,6 +21,7 @@ constexpr int KB = 64;   // keys per tile
 constexpr int TILE = KB * RP;
 constexpr float kLn2 = 0.6931471805599453f;
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -218,18 +219,31 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
 
 
 // ------------------------------------------------------------------------------------------------
-// backward, D_i = dO_i . O_i  (one wavefront per (row, head))
+// backward, D_i = dO_i . O_i.  A workgroup takes 64 consecutive rows of one head, 16 per wavefront (one row
+// per step, two elements per lane), and writes their sums as one contiguous run.
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(64) void attn_bwd128_prep_kernel(const bf16_t* __restrict__ o,
-                                                              const bf16_t* __restrict__ dout,
-                                                              float* __restrict__ dvec, int s, int a) {
-  const int i = blockIdx.x, head = blockIdx.y, bi = blockIdx.z;
-  const long off = ((long)bi * s + i) * a * D + head * D + threadIdx.x * 2;
-  float acc = 0.f;
-  if ((int)threadIdx.x * 2 < D) acc = (float)o[off] * (float)dout[off] + (float)o[off + 1] * (float)dout[off + 1];
-  acc = wave_sum(acc);
-  if (threadIdx.x == 0) dvec[((long)bi * a + head) * s + i] = acc;
+__global__ __launch_bounds__(256) void attn_bwd128_prep_kernel(const bf16_t* __restrict__ o,
+                                                               const bf16_t* __restrict__ dout,
+                                                               float* __restrict__ dvec, int s, int a) {
+  const int head = blockIdx.y, bi = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i0 = blockIdx.x * 64 + wave * 16;
+  const long off = ((long)bi * s + i0) * a * D + head * D + lane * 2;
+  const long rs = (long)a * D;
+  float mine = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float acc = 0.f;
+    if (lane * 2 < D) {
+      const bf16x2 x = *reinterpret_cast<const bf16x2*>(o + off + r * rs);
+      const bf16x2 y = *reinterpret_cast<const bf16x2*>(dout + off + r * rs);
+      acc = (float)x[0] * (float)y[0] + (float)x[1] * (float)y[1];
+    }
+    acc = wave_sum(acc);
+    if (lane == r) mine = acc;
+  }
+  if (lane < 16) dvec[((long)bi * a + head) * s + i0 + lane] = mine;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -469,20 +483,152 @@ __device__ __forceinline__ void attn_bwd128_dkv_body(unsigned char* smem_raw, in
     }
 }
 
+// dK and dV for head size 128 with two workgroups per CU: a workgroup owns 128 keys and one half (64 columns)
+// of dK and dV, so its accumulators are 64 registers instead of 128 and, with the two 32-query halves of a
+// tile taken one after the other, a wave stays under 256 registers; two workgroups (of this kind or of the dQ
+// kind) then share a CU and one's MFMAs run while the other waits for LDS or the exponentials.  S and dP are
+// computed by both halves; every dK / dV element is the same chain of MFMA additions as in the one-workgroup
+// form (tile by tile, k blocks 0..3).  Two-stage ring (tile ib+1 is fetched while ib is used).
+template <int D>
+__device__ __forceinline__ void attn_bwd128_dkv_half_body(unsigned char* smem_raw, int id, int per, int nb,
+                                                          const bf16_t* __restrict__ qkv,
+                                                          const bf16_t* __restrict__ dout,
+                                                          const float* __restrict__ lse,
+                                                          const float* __restrict__ dvec,
+                                                          bf16_t* __restrict__ dqkv, int s, int a, float scale) {
+  static_assert(D == 128, "two column halves of 64");
+  constexpr int NE = 2;  // 32-column blocks per half
+  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
+  bf16_t* sO = sQ + 2 * TILE;                        // [2][TILE]  dO tiles
+  float* sS = reinterpret_cast<float*>(sO + 2 * TILE);  // [2][4][64]: lse, D, spare, spare
+  const int half = id >= per ? 1 : 0;
+  id -= half * per;
+  int kb, head, bi;
+  map_block(id, s / QB, a, nb, false, &kb, &head, &bi);  // key block 0 has the most work
+  const int h = a * D;
+  const long ld = 3L * h;
+  const long tok0 = (long)bi * s;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int hi = lane >> 5, lk = lane & 31;
+  const int kw0 = kb * QB + wave * 32;
+  const float sl2 = scale * 1.4426950408889634f;
+
+  const int ib0 = kb * (QB / KB), nib = s / KB;
+  const bf16_t* qbase = qkv + tok0 * ld + head * D;
+  const bf16_t* obase = dout + tok0 * h + head * D;
+  const float* stat = ((wave & 1) ? dvec : lse) + ((long)bi * a + head) * s;
+  auto issue = [&](int ib) {  // 9 DMA instructions per wave
+    const int st = (ib - ib0) & 1;
+    dma_tile<D>(qbase + (long)ib * KB * ld, ld, sQ + st * TILE, wave, lane);
+    dma_tile<D>(obase + (long)ib * KB * h, h, sO + st * TILE, wave, lane);
+    __builtin_amdgcn_global_load_lds((gptr_t)(stat + ib * KB + lane), (lptr_t)(sS + (st * 4 + wave) * 64), 4, 0, 0);
+  };
+  issue(ib0);
+
+  bf16x8 kf[D / 16], vf[D / 16];
+  {
+    const bf16_t* kp = qkv + (tok0 + kw0 + lk) * ld + h + head * D + hi * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      kf[kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(kp + h + kk * 16);
+    }
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) asm volatile("" : "+v"(kf[kk]), "+v"(vf[kk]));
+  }
+  f32x16 dk[NE], dv[NE];
+#pragma unroll
+  for (int et = 0; et < NE; ++et)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dk[et][v] = dv[et][v] = 0.f;
+
+  for (int ib = ib0; ib < nib; ++ib) {
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);  // tile ib has landed
+    __builtin_amdgcn_s_barrier();          // for everyone, and everyone is done with the other stage
+    if (ib + 1 < nib) issue(ib + 1);
+    const int stage = (ib - ib0) & 1;
+    const bf16_t* qc = sQ + stage * TILE;
+    const bf16_t* oc = sO + stage * TILE;
+    const float* lc = sS + stage * 256;
+    const float* dc = lc + 64;
+    const int q0 = ib * KB;
+    if (q0 + KB - 1 >= kw0) {  // some query of the tile can see this wave's keys
+      const bool act0 = q0 + 31 >= kw0;
+      const bool diag = q0 < kw0 + 31;
+      const int mykey = kw0 + lk;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        if (t == 0 && !act0) continue;
+        f32x16 st, dpt;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[v] = dpt[v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) {
+          st = mfma(frag_rowk(qc, t * 32, kk, lane), kf[kk], st);
+          dpt = mfma(frag_rowk(oc, t * 32, kk, lane), vf[kk], dpt);
+        }
+        f32x16 pt;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int qi = t * 32 + g * 8 + hi * 4;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lc + qi);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dc + qi);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int v = g * 4 + i;
+            float p = __builtin_amdgcn_exp2f(st[v] * sl2 - l4[i] * 1.4426950408889634f);
+            if (diag && mykey > q0 + qi + i) p = 0.f;
+            pt[v] = p;
+            st[v] = p * (dpt[v] - d4[i]);
+          }
+        }
+        bf16x8 pf[2], dsf[2];
+        pf[0] = pack_half(pt, 0); pf[1] = pack_half(pt, 1);
+        dsf[0] = pack_half(st, 0); dsf[1] = pack_half(st, 1);
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+#pragma unroll
+          for (int et = 0; et < NE; ++et) {
+            const int eb = (half * NE + et) * 32;
+            dv[et] = mfma(frag_tr(oc, eb, (t * 2 + k2) * 16, lane), pf[k2], dv[et]);
+            dk[et] = mfma(frag_tr(qc, eb, (t * 2 + k2) * 16, lane), dsf[k2], dk[et]);
+          }
+        }
+      }
+    }
+  }
+  bf16_t* kp = dqkv + (tok0 + kw0 + lk) * ld + h + head * D + half * (NE * 32) + hi * 4;
+#pragma unroll
+  for (int et = 0; et < NE; ++et)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      store4(kp + et * 32 + g * 8, dk[et][4 * g] * scale, dk[et][4 * g + 1] * scale, dk[et][4 * g + 2] * scale,
+             dk[et][4 * g + 3] * scale);
+      store4(kp + h + et * 32 + g * 8, dv[et][4 * g], dv[et][4 * g + 1], dv[et][4 * g + 2], dv[et][4 * g + 3]);
+    }
+}
+
 // dK/dV and dQ in one launch: they are independent (both recompute S), and their workgroups have very
 // uneven lengths (causal: 1 to 16 tiles), so the dQ workgroups fill the CUs that the shorter dK/dV
 // workgroups leave early.  The first half of the grid is dK/dV (one workgroup per CU: it holds K, V and both
 // accumulators in registers), heaviest key blocks first; the second half dQ, heaviest query blocks first.
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd128_kernel(const bf16_t* __restrict__ qkv,
-                                                          const bf16_t* __restrict__ dout,
-                                                          const float* __restrict__ lse,
-                                                          const float* __restrict__ dvec,
-                                                          bf16_t* __restrict__ dqkv, int s, int a, int nb, float scale) {
+__global__ __launch_bounds__(256, D == 128 ? 2 : 1) void attn_bwd128_kernel(const bf16_t* __restrict__ qkv,
+                                                                            const bf16_t* __restrict__ dout,
+                                                                            const float* __restrict__ lse,
+                                                                            const float* __restrict__ dvec,
+                                                                            bf16_t* __restrict__ dqkv, int s, int a,
+                                                                            int nb, int per, float scale) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  const int per = gridDim.x >> 1;
-  if ((int)blockIdx.x < per) attn_bwd128_dkv_body<D>(smem_raw, blockIdx.x, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
-  else attn_bwd128_dq_body<D>(smem_raw, blockIdx.x - per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+  const int id = blockIdx.x;
+  if constexpr (D == 128) {
+    // 2 * per workgroups of dK/dV (column half 0, then column half 1), then per of dQ; two per CU
+    if (id < 2 * per) attn_bwd128_dkv_half_body<D>(smem_raw, id, per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+    else attn_bwd128_dq_body<D>(smem_raw, id - 2 * per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+  } else {
+    if (id < per) attn_bwd128_dkv_body<D>(smem_raw, id, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+    else attn_bwd128_dq_body<D>(smem_raw, id - per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+  }
 }
 
 template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
@@ -503,8 +649,10 @@ template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
 template <int D> hipError_t run_bwd_dma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
   constexpr size_t smem_q = (size_t)4 * TILE * sizeof(bf16_t);
-  constexpr size_t smem_kv = (size_t)6 * TILE * sizeof(bf16_t) + 3 * 4 * 64 * sizeof(float);
+  constexpr int kv_stages = D == 128 ? 2 : 3;
+  constexpr size_t smem_kv = (size_t)2 * kv_stages * TILE * sizeof(bf16_t) + kv_stages * 4 * 64 * sizeof(float);
   constexpr size_t smem = smem_kv > smem_q ? smem_kv : smem_q;
+  static_assert(D != 128 || 2 * smem <= 160 * 1024, "two workgroups per CU");
   if (!done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -512,13 +660,13 @@ template <int D> hipError_t run_bwd_dma(const AttnArgs& a, hipStream_t s) {
     done = true;
   }
   const float scale = 1.0f / sqrtf((float)D);
-  dim3 grid1(a.s, a.a, a.b);
-  attn_bwd128_prep_kernel<D><<<grid1, 64, 0, s>>>((const bf16_t*)a.o, (const bf16_t*)a.dout, a.dvec, a.s, a.a);
+  dim3 grid1(a.s / 64, a.a, a.b);
+  attn_bwd128_prep_kernel<D><<<grid1, 256, 0, s>>>((const bf16_t*)a.o, (const bf16_t*)a.dout, a.dvec, a.s, a.a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int per = (a.s / QB) * a.a * a.b;
-  attn_bwd128_kernel<D><<<2 * per, 256, smem, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse, a.dvec,
-                                                   (bf16_t*)a.dqkv, a.s, a.a, a.b, scale);
+  attn_bwd128_kernel<D><<<(D == 128 ? 3 : 2) * per, 256, smem, s>>>((const bf16_t*)a.qkv, (const bf16_t*)a.dout, a.lse,
+                                                                    a.dvec, (bf16_t*)a.dqkv, a.s, a.a, a.b, per, scale);
   return hipGetLastError();
 }
 
