@@ -250,14 +250,12 @@ __global__ __launch_bounds__(256) void attn_bwd128_prep_kernel(const bf16_t* __r
 // backward, dQ: workgroup = 128 queries, loop over key tiles up to the diagonal (same pipeline as forward)
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__device__ __forceinline__ void attn_bwd128_dq_body(unsigned char* smem_raw, int id, int nb,
+__device__ __forceinline__ void attn_bwd128_dq_body(unsigned char* smem_raw, int qb, int head, int bi,
                                                     const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                     const float* __restrict__ lse, const float* __restrict__ dvec,
                                                     bf16_t* __restrict__ dqkv, int s, int a, float scale) {
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
   bf16_t* sV = sK + 2 * TILE;                        // [2][TILE]
-  int qb, head, bi;
-  map_block(id, s / QB, a, nb, true, &qb, &head, &bi);
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
@@ -361,15 +359,13 @@ __device__ __forceinline__ void attn_bwd128_dq_body(unsigned char* smem_raw, int
 // wave has the same number of loads in flight).
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__device__ __forceinline__ void attn_bwd128_dkv_body(unsigned char* smem_raw, int id, int nb,
+__device__ __forceinline__ void attn_bwd128_dkv_body(unsigned char* smem_raw, int kb, int head, int bi,
                                                      const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                      const float* __restrict__ lse, const float* __restrict__ dvec,
                                                      bf16_t* __restrict__ dqkv, int s, int a, float scale) {
   bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [3][TILE]
   bf16_t* sO = sQ + 3 * TILE;                        // [3][TILE]  dO tiles
   float* sS = reinterpret_cast<float*>(sO + 3 * TILE);  // [3][4][64]: lse, D, spare, spare
-  int kb, head, bi;
-  map_block(id, s / QB, a, nb, false, &kb, &head, &bi);  // key block 0 has the most work
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
@@ -490,7 +486,7 @@ __device__ __forceinline__ void attn_bwd128_dkv_body(unsigned char* smem_raw, in
 // computed by both halves; every dK / dV element is the same chain of MFMA additions as in the one-workgroup
 // form (tile by tile, k blocks 0..3).  Two-stage ring (tile ib+1 is fetched while ib is used).
 template <int D>
-__device__ __forceinline__ void attn_bwd128_dkv_half_body(unsigned char* smem_raw, int id, int per, int nb,
+__device__ __forceinline__ void attn_bwd128_dkv_half_body(unsigned char* smem_raw, int kb, int half, int head, int bi,
                                                           const bf16_t* __restrict__ qkv,
                                                           const bf16_t* __restrict__ dout,
                                                           const float* __restrict__ lse,
@@ -501,10 +497,6 @@ __device__ __forceinline__ void attn_bwd128_dkv_half_body(unsigned char* smem_ra
   bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
   bf16_t* sO = sQ + 2 * TILE;                        // [2][TILE]  dO tiles
   float* sS = reinterpret_cast<float*>(sO + 2 * TILE);  // [2][4][64]: lse, D, spare, spare
-  const int half = id >= per ? 1 : 0;
-  id -= half * per;
-  int kb, head, bi;
-  map_block(id, s / QB, a, nb, false, &kb, &head, &bi);  // key block 0 has the most work
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
@@ -609,8 +601,10 @@ __device__ __forceinline__ void attn_bwd128_dkv_half_body(unsigned char* smem_ra
 }
 
 // dK/dV and dQ in one launch: they are independent (both recompute S), and their workgroups have very
-// uneven lengths (causal: 1 to 16 tiles), so the dQ workgroups fill the CUs that the shorter dK/dV
-// workgroups leave early.  The first half of the grid is dK/dV (one workgroup per CU: it holds K, V and both
+// uneven lengths (causal: 1 to 16 tiles), so short workgroups of one kind fill the CUs that the other kind
+// leaves early.  Head size 128: two workgroups per CU; per head three workgroups for each block index
+// (dK/dV column half 0, half 1, dQ), issued heaviest block first over all three kinds, every head on one XCD.
+// Other head sizes: the first half of the grid is dK/dV (one workgroup per CU: it holds K, V and both
 // accumulators in registers), heaviest key blocks first; the second half dQ, heaviest query blocks first.
 template <int D>
 __global__ __launch_bounds__(256, D == 128 ? 2 : 1) void attn_bwd128_kernel(const bf16_t* __restrict__ qkv,
@@ -620,14 +614,29 @@ __global__ __launch_bounds__(256, D == 128 ? 2 : 1) void attn_bwd128_kernel(cons
                                                                             bf16_t* __restrict__ dqkv, int s, int a,
                                                                             int nb, int per, float scale) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  const int id = blockIdx.x;
+  const int id = blockIdx.x, nrb = s / QB;
+  int blk, head, bi;
   if constexpr (D == 128) {
-    // 2 * per workgroups of dK/dV (column half 0, then column half 1), then per of dQ; two per CU
-    if (id < 2 * per) attn_bwd128_dkv_half_body<D>(smem_raw, id, per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
-    else attn_bwd128_dq_body<D>(smem_raw, id - 2 * per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+    const int heads = a * nb;
+    int kind;  // 0, 1: dK/dV column half; 2: dQ
+    if ((heads & 7) == 0) {
+      const int xcd = id & 7, local = id >> 3, hpx = heads >> 3;
+      const int level = local / (3 * hpx), rem = local - level * 3 * hpx;  // level 0: the blocks with the most tiles
+      kind = rem / hpx;
+      const int hl = (rem - kind * hpx) * 8 + xcd;
+      blk = kind < 2 ? level : nrb - 1 - level;
+      head = hl % a;
+      bi = hl / a;
+    } else {
+      kind = id / per;
+      map_block(id - kind * per, nrb, a, nb, kind == 2, &blk, &head, &bi);
+    }
+    if (kind < 2) attn_bwd128_dkv_half_body<D>(smem_raw, blk, kind, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
+    else attn_bwd128_dq_body<D>(smem_raw, blk, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
   } else {
-    if (id < per) attn_bwd128_dkv_body<D>(smem_raw, id, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
-    else attn_bwd128_dq_body<D>(smem_raw, id - per, nb, qkv, dout, lse, dvec, dqkv, s, a, scale);
+    map_block(id < per ? id : id - per, nrb, a, nb, id >= per, &blk, &head, &bi);
+    if (id < per) attn_bwd128_dkv_body<D>(smem_raw, blk, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
+    else attn_bwd128_dq_body<D>(smem_raw, blk, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
   }
 }
 
