@@ -358,142 +358,22 @@ __device__ __forceinline__ void attn_bwd128_dq_body(unsigned char* smem_raw, int
 // statistics (waves 0/1 fetch lse / D, waves 2/3 fetch the same again into a spare area so that every
 // wave has the same number of loads in flight).
 // ------------------------------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ void attn_bwd128_dkv_body(unsigned char* smem_raw, int kb, int head, int bi,
-                                                     const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
-                                                     const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                     bf16_t* __restrict__ dqkv, int s, int a, float scale) {
-  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [3][TILE]
-  bf16_t* sO = sQ + 3 * TILE;                        // [3][TILE]  dO tiles
-  float* sS = reinterpret_cast<float*>(sO + 3 * TILE);  // [3][4][64]: lse, D, spare, spare
-  const int h = a * D;
-  const long ld = 3L * h;
-  const long tok0 = (long)bi * s;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int hi = lane >> 5, lk = lane & 31;
-  const int kw0 = kb * QB + wave * 32;
-  const float sl2 = scale * 1.4426950408889634f;
-
-  const int ib0 = kb * (QB / KB), nib = s / KB;
-  const bf16_t* qbase = qkv + tok0 * ld + head * D;
-  const bf16_t* obase = dout + tok0 * h + head * D;
-  const float* stat = ((wave & 1) ? dvec : lse) + ((long)bi * a + head) * s;
-  auto issue = [&](int ib) {  // 9 DMA instructions per wave
-    const int st = (ib - ib0) % 3;
-    dma_tile<D>(qbase + (long)ib * KB * ld, ld, sQ + st * TILE, wave, lane);
-    dma_tile<D>(obase + (long)ib * KB * h, h, sO + st * TILE, wave, lane);
-    __builtin_amdgcn_global_load_lds((gptr_t)(stat + ib * KB + lane), (lptr_t)(sS + (st * 4 + wave) * 64), 4, 0, 0);
-  };
-  issue(ib0);
-  if (ib0 + 1 < nib) issue(ib0 + 1);
-
-  bf16x8 kf[D / 16], vf[D / 16];
-  {
-    const bf16_t* kp = qkv + (tok0 + kw0 + lk) * ld + h + head * D + hi * 8;
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      kf[kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
-      vf[kk] = *reinterpret_cast<const bf16x8*>(kp + h + kk * 16);
-    }
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) asm volatile("" : "+v"(kf[kk]), "+v"(vf[kk]));
-  }
-  f32x16 dk[D / 32], dv[D / 32];
-#pragma unroll
-  for (int et = 0; et < D / 32; ++et)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) dk[et][v] = dv[et][v] = 0.f;
-
-  for (int ib = ib0; ib < nib; ++ib) {
-    if (ib + 1 < nib) __builtin_amdgcn_s_waitcnt(9 | (7 << 4) | (15 << 8));
-    else __builtin_amdgcn_s_waitcnt(kWaitVm0);
-    __builtin_amdgcn_s_barrier();
-    if (ib + 2 < nib) issue(ib + 2);
-    const int stage = (ib - ib0) % 3;
-    const bf16_t* qc = sQ + stage * TILE;
-    const bf16_t* oc = sO + stage * TILE;
-    const float* lc = sS + stage * 256;
-    const float* dc = lc + 64;
-    const int q0 = ib * KB;
-    if (q0 + KB - 1 >= kw0) {  // some query of the tile can see this wave's keys
-      const bool act0 = q0 + 31 >= kw0;
-      f32x16 st[2], dpt[2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) st[t][v] = dpt[t][v] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        if (act0) {
-          st[0] = mfma(frag_rowk(qc, 0, kk, lane), kf[kk], st[0]);
-          dpt[0] = mfma(frag_rowk(oc, 0, kk, lane), vf[kk], dpt[0]);
-        }
-        st[1] = mfma(frag_rowk(qc, 32, kk, lane), kf[kk], st[1]);
-        dpt[1] = mfma(frag_rowk(oc, 32, kk, lane), vf[kk], dpt[1]);
-      }
-      const bool diag = q0 < kw0 + 31;
-      const int mykey = kw0 + lk;
-      f32x16 pt[2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int qi = t * 32 + g * 8 + hi * 4;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lc + qi);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dc + qi);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int v = g * 4 + i;
-            float p = __builtin_amdgcn_exp2f(st[t][v] * sl2 - l4[i] * 1.4426950408889634f);
-            if (diag && mykey > q0 + qi + i) p = 0.f;
-            if (t == 0 && !act0) p = 0.f;
-            pt[t][v] = p;
-            st[t][v] = p * (dpt[t][v] - d4[i]);
-          }
-        }
-      bf16x8 pf[4], dsf[4];
-      pf[0] = pack_half(pt[0], 0); pf[1] = pack_half(pt[0], 1);
-      pf[2] = pack_half(pt[1], 0); pf[3] = pack_half(pt[1], 1);
-      dsf[0] = pack_half(st[0], 0); dsf[1] = pack_half(st[0], 1);
-      dsf[2] = pack_half(st[1], 0); dsf[3] = pack_half(st[1], 1);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        if (kk >= 2 || act0) {
-#pragma unroll
-          for (int et = 0; et < D / 32; ++et) {
-            dv[et] = mfma(frag_tr(oc, et * 32, kk * 16, lane), pf[kk], dv[et]);
-            dk[et] = mfma(frag_tr(qc, et * 32, kk * 16, lane), dsf[kk], dk[et]);
-          }
-        }
-      }
-    }
-  }
-  bf16_t* kp = dqkv + (tok0 + kw0 + lk) * ld + h + head * D + hi * 4;
-#pragma unroll
-  for (int et = 0; et < D / 32; ++et)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      store4(kp + et * 32 + g * 8, dk[et][4 * g] * scale, dk[et][4 * g + 1] * scale, dk[et][4 * g + 2] * scale,
-             dk[et][4 * g + 3] * scale);
-      store4(kp + h + et * 32 + g * 8, dv[et][4 * g], dv[et][4 * g + 1], dv[et][4 * g + 2], dv[et][4 * g + 3]);
-    }
-}
-
-// dK and dV for head size 128 with two workgroups per CU: a workgroup owns 128 keys and one half (64 columns)
-// of dK and dV, so its accumulators are 64 registers instead of 128 and, with the two 32-query halves of a
-// tile taken one after the other, a wave stays under 256 registers; two workgroups (of this kind or of the dQ
-// kind) then share a CU and one's MFMAs run while the other waits for LDS or the exponentials.  S and dP are
-// computed by both halves; every dK / dV element is the same chain of MFMA additions as in the one-workgroup
-// form (tile by tile, k blocks 0..3).  Two-stage ring (tile ib+1 is fetched while ib is used).
-template <int D>
+// dK and dV with two workgroups per CU: a workgroup owns 128 keys and, of dK and dV, the D / NH columns of
+// column part `half` (head size 128: NH = 2 halves of 64 columns, 64 accumulator registers instead of 128;
+// head size 96: NH = 1, all 96).  With the two 32-query halves of a tile taken one after the other a wave
+// stays under 256 registers; two workgroups (of this kind or of the dQ kind) then share a CU and one's MFMAs
+// run while the other waits for LDS or the exponentials.  With NH = 2, S and dP are computed by both halves;
+// every dK / dV element is the same chain of MFMA additions whatever NH (tile by tile, k blocks 0..3).
+// Two-stage ring (tile ib+1 is fetched while ib is used).
+template <int D, int NH>
 __device__ __forceinline__ void attn_bwd128_dkv_half_body(unsigned char* smem_raw, int kb, int half, int head, int bi,
                                                           const bf16_t* __restrict__ qkv,
                                                           const bf16_t* __restrict__ dout,
                                                           const float* __restrict__ lse,
                                                           const float* __restrict__ dvec,
                                                           bf16_t* __restrict__ dqkv, int s, int a, float scale) {
-  static_assert(D == 128, "two column halves of 64");
-  constexpr int NE = 2;  // 32-column blocks per half
+  static_assert((D / 32) % NH == 0, "whole 32-column blocks per workgroup");
+  constexpr int NE = D / 32 / NH;  // 32-column blocks of dK and dV this workgroup owns
   bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
   bf16_t* sO = sQ + 2 * TILE;                        // [2][TILE]  dO tiles
   float* sS = reinterpret_cast<float*>(sO + 2 * TILE);  // [2][4][64]: lse, D, spare, spare
@@ -602,42 +482,34 @@ __device__ __forceinline__ void attn_bwd128_dkv_half_body(unsigned char* smem_ra
 
 // dK/dV and dQ in one launch: they are independent (both recompute S), and their workgroups have very
 // uneven lengths (causal: 1 to 16 tiles), so short workgroups of one kind fill the CUs that the other kind
-// leaves early.  Head size 128: two workgroups per CU; per head three workgroups for each block index
-// (dK/dV column half 0, half 1, dQ), issued heaviest block first over all three kinds, every head on one XCD.
-// Other head sizes: the first half of the grid is dK/dV (one workgroup per CU: it holds K, V and both
-// accumulators in registers), heaviest key blocks first; the second half dQ, heaviest query blocks first.
+// leaves early.  Two workgroups per CU; per head NH + 1 workgroups for each block index (the NH column parts
+// of dK/dV, then dQ), issued heaviest block first over all kinds, every head on one XCD.
 template <int D>
-__global__ __launch_bounds__(256, D == 128 ? 2 : 1) void attn_bwd128_kernel(const bf16_t* __restrict__ qkv,
-                                                                            const bf16_t* __restrict__ dout,
-                                                                            const float* __restrict__ lse,
-                                                                            const float* __restrict__ dvec,
-                                                                            bf16_t* __restrict__ dqkv, int s, int a,
-                                                                            int nb, int per, float scale) {
+__global__ __launch_bounds__(256, 2) void attn_bwd128_kernel(const bf16_t* __restrict__ qkv,
+                                                             const bf16_t* __restrict__ dout,
+                                                             const float* __restrict__ lse,
+                                                             const float* __restrict__ dvec,
+                                                             bf16_t* __restrict__ dqkv, int s, int a, int nb, int per,
+                                                             float scale) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
+  constexpr int NH = D == 128 ? 2 : 1, NK = NH + 1;
   const int id = blockIdx.x, nrb = s / QB;
-  int blk, head, bi;
-  if constexpr (D == 128) {
-    const int heads = a * nb;
-    int kind;  // 0, 1: dK/dV column half; 2: dQ
-    if ((heads & 7) == 0) {
-      const int xcd = id & 7, local = id >> 3, hpx = heads >> 3;
-      const int level = local / (3 * hpx), rem = local - level * 3 * hpx;  // level 0: the blocks with the most tiles
-      kind = rem / hpx;
-      const int hl = (rem - kind * hpx) * 8 + xcd;
-      blk = kind < 2 ? level : nrb - 1 - level;
-      head = hl % a;
-      bi = hl / a;
-    } else {
-      kind = id / per;
-      map_block(id - kind * per, nrb, a, nb, kind == 2, &blk, &head, &bi);
-    }
-    if (kind < 2) attn_bwd128_dkv_half_body<D>(smem_raw, blk, kind, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
-    else attn_bwd128_dq_body<D>(smem_raw, blk, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
+  const int heads = a * nb;
+  int blk, head, bi, kind;  // kind < NH: dK/dV column part; NH: dQ
+  if ((heads & 7) == 0) {
+    const int xcd = id & 7, local = id >> 3, hpx = heads >> 3;
+    const int level = local / (NK * hpx), rem = local - level * NK * hpx;  // level 0: the blocks with the most tiles
+    kind = rem / hpx;
+    const int hl = (rem - kind * hpx) * 8 + xcd;
+    blk = kind < NH ? level : nrb - 1 - level;
+    head = hl % a;
+    bi = hl / a;
   } else {
-    map_block(id < per ? id : id - per, nrb, a, nb, id >= per, &blk, &head, &bi);
-    if (id < per) attn_bwd128_dkv_body<D>(smem_raw, blk, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
-    else attn_bwd128_dq_body<D>(smem_raw, blk, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
+    kind = id / per;
+    map_block(id - kind * per, nrb, a, nb, kind == NH, &blk, &head, &bi);
   }
+  if (kind < NH) attn_bwd128_dkv_half_body<D, NH>(smem_raw, blk, kind, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
+  else attn_bwd128_dq_body<D>(smem_raw, blk, head, bi, qkv, dout, lse, dvec, dqkv, s, a, scale);
 }
 
 template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
@@ -658,10 +530,10 @@ template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
 template <int D> hipError_t run_bwd_dma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
   constexpr size_t smem_q = (size_t)4 * TILE * sizeof(bf16_t);
-  constexpr int kv_stages = D == 128 ? 2 : 3;
+  constexpr int kv_stages = 2;
   constexpr size_t smem_kv = (size_t)2 * kv_stages * TILE * sizeof(bf16_t) + kv_stages * 4 * 64 * sizeof(float);
   constexpr size_t smem = smem_kv > smem_q ? smem_kv : smem_q;
-  static_assert(D != 128 || 2 * smem <= 160 * 1024, "two workgroups per CU");
+  static_assert(2 * smem <= 160 * 1024, "two workgroups per CU");
   if (!done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd128_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
