@@ -153,8 +153,10 @@ __global__ void decide_validate_kernel(OptDevState* st, OptHyper hp, double prev
 
 // bookkeeping between the rollback and the redo
 __global__ void decide_after_rollback_kernel(OptDevState* st, OptHyper hp) {
-  // after a rollback theta, m, v equal the journal: the redo need not write it again
-  if (st->do_rollback) { st->t -= 1; st->do_rollback = 0; st->journal_current = 1; }
+  // A step taken after the validation is final (nothing can roll it back), so it writes no journal: the redo
+  // after a rollback (theta, m, v equal the journal anyway) and the deferred clipped step alike.
+  if (st->do_rollback) { st->t -= 1; st->do_rollback = 0; }
+  st->journal_current = 1;
   if (st->do_step) advance_time(st, hp);
 }
 

@@ -1146,7 +1146,7 @@ zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, z
   }
   ZB_HIP(st, launch_decide_after_rollback(st->opt, st->hp, s));
   {
-    ProfScope ps(st, KC_ADAMW_RESTEP, 0, step_bytes);
+    ProfScope ps(st, KC_ADAMW_RESTEP, 0, n_d * (16 + 12 + (st->theta16 ? 2 : 0)));  // no journal after the validation
     ZB_HIP(st, launch_adamw_step(st->theta, st->adam_m, st->adam_v, st->grad, st->j_theta, st->j_m, st->j_v,
                                  st->theta16, n, st->hp, st->opt, s));
   }

@@ -224,7 +224,7 @@ struct OptDevState {
   int outcome;
   float step_coef;       // gradient scale of the next step kernel
   float bc1, bc2;        // 1 - beta1^t, 1 - beta2^t for the step / rollback at time t
-  int journal_current;   // the journal already holds theta, m, v as they are now (just restored from it)
+  int journal_current;   // the next step writes no journal: it comes after the validation (final), and after a rollback theta, m, v equal the journal anyway
 };
 
 struct OptHyper {
