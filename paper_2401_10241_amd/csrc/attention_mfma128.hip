@@ -100,26 +100,34 @@ __device__ __forceinline__ void map_block(int id, int nrb, int a, int b, bool fi
   *bi = hl / a;
 }
 
+// Forward.  A workgroup owns 128 query rows of one head and has eight waves in two groups of four: group g
+// takes the key tiles g, g + 2, ... (a causal row block has an even number of 64-key tiles, so both groups get
+// the same number), each with its own running maximum, sum and output accumulators, and at the end group 0
+// merges group 1's state into its own (the usual rescaling by 2^(m_g - m)) and writes the rows.  The chain of
+// dependent tiles of the heaviest row block is then 8 long instead of 16, and the two groups' waves share
+// the SIMDs, one's MFMAs running while the other is in its softmax.  Each group has a two-stage ring of K and
+// V tiles (128 KB in all, one workgroup per CU); group 1's state travels through the same memory.
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(512, 2) void attn_fwd128_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                              float* __restrict__ lse, int s, int a, float sl2) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);  // [2][TILE]
-  bf16_t* sV = sK + 2 * TILE;                        // [2][TILE]
   int qb, head, bi;
   map_block(blockIdx.x, s / QB, a, gridDim.x / (a * (s / QB)), true, &qb, &head, &bi);  // heaviest blocks first
   const int h = a * D;
   const long ld = 3L * h;
   const long tok0 = (long)bi * s;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave8 = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int grp = wave8 >> 2, wave = wave8 & 3;
   const int hi = lane >> 5, lq = lane & 31;
   const int qw0 = qb * QB + wave * 32;
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw) + grp * 4 * TILE;  // this group's [2][TILE]
+  bf16_t* sV = sK + 2 * TILE;                                         // and its [2][TILE]
 
-  const int nkb = 2 * qb + 2;
+  const int nit = qb + 1;  // tiles per group
   const bf16_t* kbase = qkv + tok0 * ld + h + head * D;
   const bf16_t* vbase = kbase + h;
-  dma_tile<D>(kbase, ld, sK, wave, lane);
-  dma_tile<D>(vbase, ld, sV, wave, lane);
+  dma_tile<D>(kbase + (long)grp * KB * ld, ld, sK, wave, lane);
+  dma_tile<D>(vbase + (long)grp * KB * ld, ld, sV, wave, lane);
 
   bf16x8 qf[D / 16];
   {
@@ -137,15 +145,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
     for (int v = 0; v < 16; ++v) o[et][v] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  for (int jb = 0; jb < nkb; ++jb) {
+  for (int i = 0; i < nit; ++i) {
+    const int jb = 2 * i + grp;
     __builtin_amdgcn_s_waitcnt(kWaitVm0);  // this wave's part of tile jb has landed
     __builtin_amdgcn_s_barrier();          // everyone's has; everyone is done with the other stage
-    if (jb + 1 < nkb) {
-      dma_tile<D>(kbase + (long)(jb + 1) * KB * ld, ld, sK + ((jb + 1) & 1) * TILE, wave, lane);
-      dma_tile<D>(vbase + (long)(jb + 1) * KB * ld, ld, sV + ((jb + 1) & 1) * TILE, wave, lane);
+    if (i + 1 < nit) {
+      dma_tile<D>(kbase + (long)(jb + 2) * KB * ld, ld, sK + ((i + 1) & 1) * TILE, wave, lane);
+      dma_tile<D>(vbase + (long)(jb + 2) * KB * ld, ld, sV + ((i + 1) & 1) * TILE, wave, lane);
     }
-    const bf16_t* kc = sK + (jb & 1) * TILE;
-    const bf16_t* vc = sV + (jb & 1) * TILE;
+    const bf16_t* kc = sK + (i & 1) * TILE;
+    const bf16_t* vc = sV + (i & 1) * TILE;
     const int key0 = jb * KB;
     if (key0 <= qw0 + 31) {  // this wave still has unmasked keys in the tile
       const bool act1 = key0 + 32 <= qw0 + 31;
@@ -204,6 +213,34 @@ __global__ __launch_bounds__(256, 2) void attn_fwd128_kernel(const bf16_t* __res
         }
       }
     }
+  }
+
+  // group 1 hands its state to group 0 through LDS: [wave][register][lane] floats, then m and l
+  constexpr int NR = (D / 32) * 16;
+  float* xo = reinterpret_cast<float*>(smem_raw);  // [4][NR][64]
+  float* xm = xo + 4 * NR * 64;                    // [4][2][64]
+  __builtin_amdgcn_s_barrier();  // every wave is done with the rings (no load is in flight: the last wait was for all)
+  if (grp == 1) {
+#pragma unroll
+    for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) xo[(wave * NR + et * 16 + v) * 64 + lane] = o[et][v];
+    xm[(wave * 2 + 0) * 64 + lane] = m;
+    xm[(wave * 2 + 1) * 64 + lane] = l;
+  }
+  __syncthreads();
+  if (grp == 1) return;
+  {
+    // a wave of group 1 that saw no unmasked key has m = -inf, l = 0, o = 0: its factor is 0
+    const float m1 = xm[(wave * 2 + 0) * 64 + lane], l1 = xm[(wave * 2 + 1) * 64 + lane];
+    const float m_new = fmaxf(m, m1);  // group 0 always holds key 0: finite
+    const float a0 = __builtin_amdgcn_exp2f(m - m_new), a1 = __builtin_amdgcn_exp2f(m1 - m_new);
+    l = l * a0 + l1 * a1;
+    m = m_new;
+#pragma unroll
+    for (int et = 0; et < D / 32; ++et)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[et][v] = o[et][v] * a0 + xo[(wave * NR + et * 16 + v) * 64 + lane] * a1;
   }
 
   const float inv = 1.0f / l;
@@ -514,7 +551,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd128_kernel(const bf16_t* __res
 
 template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
   static bool done = false;
-  constexpr size_t smem = (size_t)4 * TILE * sizeof(bf16_t);
+  constexpr size_t smem = (size_t)8 * TILE * sizeof(bf16_t);  // two groups x (K, V) x two stages
+  static_assert(smem >= ((size_t)4 * (D / 32) * 16 * 64 + 4 * 2 * 64) * sizeof(float), "group 1's state fits");
   if (!done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd128_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -522,7 +560,7 @@ template <int D> hipError_t run_fwd_dma(const AttnArgs& a, hipStream_t s) {
     done = true;
   }
   dim3 grid((a.s / QB) * a.a * a.b);
-  attn_fwd128_kernel<D><<<grid, 256, smem, s>>>((const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.s, a.a,
+  attn_fwd128_kernel<D><<<grid, 512, smem, s>>>((const bf16_t*)a.qkv, (bf16_t*)a.out, a.lse, a.s, a.a,
                                                 1.4426950408889634f / sqrtf((float)D));
   return hipGetLastError();
 }
