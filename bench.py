@@ -109,6 +109,62 @@ def auto_schedule_report(zb, st, w, m, class_ms):
             "search_host_ms": round(search_ms, 2)}
 
 
+def paired_w_report(zb, st, w, m, kind, paired_ops, flops, auto, class_ms):
+    """The same iteration with the W passes of the order's steady state run two at a time (zb_order_pair_w;
+    Sec. 2: a W may run anywhere after its B, Appendix A): not the order `value` is measured on, reported
+    beside it.  Two W in one launch read and write every gradient once, so the W class gets faster on one
+    GPU; the p-stage timing model, fed with the measured time of a W that opens a run of W (t_w_first) and of
+    one that follows another (t_w_next), says what that does to a whole pipeline of such stages."""
+    import torch
+    import zb_inputs
+
+    def step(it):
+        st.begin_iteration(it, m)
+        st.run_order(paired_ops)
+        if w.optimizer:
+            st.optimizer_step_validated(0.0, zb_inputs.rest_state(w, it), want_report=False)
+
+    step(100)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = 3
+    for i in range(n):
+        step(101 + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / n * 1e3
+    st.profile_enable(True)
+    step(110)
+    pstats = {r["name"]: r for r in st.profile_read()}
+    st.profile_enable(False)
+    wg = pstats["gemm_wgrad"]
+
+    def runs_of_w(ops):
+        return sum(1 for i, (c, _) in enumerate(ops) if c == 2 and (i == 0 or ops[i - 1][0] != 2))
+
+    base_ops = zb.schedule_order(w.p, w.stage, m, kind)
+    r0, r1 = runs_of_w(base_ops), runs_of_w(paired_ops)
+    T0, T1 = class_ms["gemm_wgrad"] + class_ms.get("bias_grad_colsum", 0), wg["total_ms"]
+    # T = runs * t_first + (m - runs) * t_next for the two orders of this stage
+    det = r0 * (m - r1) - r1 * (m - r0)
+    rep = {"value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(ms, 3),
+           "steps": n, "gemm_wgrad": {"launches": wg["launches"], "total_ms": round(wg["total_ms"], 3),
+                                      "tflops": round(wg["flops"] / wg["total_ms"] / 1e9, 1)},
+           "w_stash_slots": zb.order_stash_need(paired_ops)[1], "w_stash_slots_unpaired": zb.order_stash_need(base_ops)[1]}
+    if det != 0:
+        t_first = (T0 * (m - r1) - T1 * (m - r0)) / det
+        t_next = (r0 * T1 - r1 * T0) / det
+        t_f, t_b, t_comm = auto["t_f_ms"], auto["t_b_ms"], auto["t_comm_ms"]
+        if t_first > 0 and t_next >= 0:
+            base_all = [zb.schedule_order(w.p, i, m, kind) for i in range(w.p)]
+            pair_all = [zb.order_pair_w(o) for o in base_all]
+            c0 = zb.simulate_pipeline_w_runs(base_all, t_f, t_b, t_first, t_comm, t_next)[0]
+            c1 = zb.simulate_pipeline_w_runs(pair_all, t_f, t_b, t_first, t_comm, t_next)[0]
+            rep["pipeline_model"] = {"t_w_first_ms": round(t_first, 4), "t_w_next_ms": round(t_next, 4),
+                                     "iteration_ms": round(c0, 3), "iteration_ms_w_paired": round(c1, 3),
+                                     "speedup": round(c0 / c1, 4)}
+    return rep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,6 +181,10 @@ def main():
                     help="hold the order's W passes back until this many can run side by side (zb_order_group_w: "
                          "same results bit for bit, group-1 more microbatches of W stash); 1 = the order as the "
                          "paper gives it (default)")
+    ap.add_argument("--w-pair", action="store_true",
+                    help="run the order with the W passes of its steady state two at a time (zb_order_pair_w: same "
+                         "results bit for bit, one more microbatch of W stash); without this flag the default "
+                         "workload also measures that order, untimed for `value`, and reports it as `w_paired`")
     ap.add_argument("--role", default="middle", choices=["middle", "first", "last"],
                     help="first / last stage of the pipeline (Sec. 5.1): one transformer layer fewer than the "
                          "workload's middle stage, plus the embedding lookup (first) or the final LayerNorm, head "
@@ -168,9 +228,18 @@ def main():
     elif args.w_group > 1:
         v_ops = zb.order_group_w(zb.schedule_order(w.p, w.stage, m, kind), args.w_group)
         pb, pw, fl = zb.order_stash_need(v_ops)
+    elif args.w_pair:
+        v_ops = zb.order_pair_w(zb.schedule_order(w.p, w.stage, m, kind))
+        pb, pw, fl = zb.order_stash_need(v_ops)
     else:
         pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, kind)
-    explicit = zbv or args.w_group > 1
+    explicit = zbv or args.w_group > 1 or args.w_pair
+    # the default run also measures the paired-W order afterwards, on the same stage: give the pools its slots
+    also_paired = not explicit and args.order == "workload" and args.role == "middle" and not args.no_profile and not args.m
+    if also_paired:
+        paired_ops = zb.order_pair_w(zb.schedule_order(w.p, w.stage, m, kind))
+        pb2, pw2, fl2 = zb.order_stash_need(paired_ops)
+        pb, pw, fl = max(pb, pb2), max(pw, pw2), max(fl, fl2)
     m_run = 2 * m if zbv else m          # virtual microbatches (chunk * m + microbatch) under ZB-V
     st = zb.Stage(role=args.role, vocab=vocab, fuse_bw=(args.order == "1F1B-fused"), chunks=(2 if zbv else 1), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
                   dtype=w.dtype, max_microbatches=m_run, max_pending_b=pb, max_pending_w=pw, max_inflight=fl,
@@ -234,6 +303,7 @@ def main():
         "config": {"workload": f"{w.name}: " + (f"{args.role} " if args.role != "middle" else "") + f"stage {w.stage} of p={w.p}, "
                                + (f"ZB-{w.kind}" if args.order == "workload" else args.order)
                                + (f" order with W held back into groups of {args.w_group}" if args.w_group > 1
+                                  else " order with steady-state W passes two at a time" if args.w_pair
                                   else " order") + f", m={m}, {w.layers} GPT "
                                f"decoder layers h={w.hidden} a={w.heads} ffn={w.ffn} seq={w.seq} b={w.mb_size}"
                                + (", validated AdamW step" if w.optimizer else ""),
@@ -307,6 +377,9 @@ def main():
             out["optimizer_forced_rollback"] = fr
         out["kernels"] = kern
         out["auto_schedule"] = auto_schedule_report(zb, st, w, m, {r["name"]: r["total_ms"] for r in stats})
+        if also_paired:
+            out["w_paired"] = paired_w_report(zb, st, w, m, kind, paired_ops, flops, out["auto_schedule"],
+                                              {r["name"]: r["total_ms"] for r in stats})
     st.close()
     del st
     torch.cuda.empty_cache()

@@ -252,6 +252,22 @@ zb_status zb_simulate_pipeline_v(int32_t p, int32_t m, const zb_op* orders, cons
  * whatever the p-stage timing model says about the bubbles.  ops and out: n entries each (host), group >= 1. */
 zb_status zb_order_group_w(const zb_op* ops, int32_t n, int32_t group, zb_op* out);
 
+/* The same stage order with the W passes of its 1F1B-shaped steady state run two at a time (Sec. 2: a W may
+ * run anywhere after its B; Appendix A): wherever the order reads  B W F_j B W  with an even microbatch j of
+ * the forward, the first W waits for the second,  B F_j B W W.  Keyed on the forward's microbatch, all
+ * stages of a pipeline pair around the same forwards, so no stage wants a tensor earlier than its neighbour,
+ * pairing the same way, sends it: at zero transfer time the timing model's cost does not grow (at most one
+ * t_comm per pair otherwise), while two W side by side read and write every gradient once
+ * (zb_backward_weight_group; zb_run_order runs consecutive W that way).  F, B and W each keep their
+ * sequence, so results keep every bit; one more W stash is pending at the peak (zb_order_stash_need on the
+ * result).  ops and out: n entries each (host). */
+zb_status zb_order_pair_w(const zb_op* ops, int32_t n, zb_op* out);
+
+/* zb_simulate_pipeline's model with one more time: a W that directly follows another W on its stage takes
+ * t_w_next >= 0 (measured: the second W of a two-W launch).  No fused backward; *cost = largest stage span. */
+zb_status zb_simulate_pipeline_w_runs(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times,
+                                      double t_w_next, double* cost, double* stage_span);
+
 /* Peak of Appendix G's memory walk over one stage order of n entries. */
 zb_status zb_order_memory_peak(const zb_op* ops, int32_t n, double m_b, double m_w, double* peak);
 

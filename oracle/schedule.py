@@ -103,13 +103,36 @@ def stash_profile(ops: Sequence[Op], M_B: float = 1.0, M_W: float = 0.0):
     return peak, at[0], at[1], max_b, max_w
 
 
+def pair_w(ops: Sequence[Op]) -> List[Op]:
+    """W passes of the 1F1B-shaped steady state run two at a time (Sec. 2: a W may run anywhere after its B;
+    Appendix A regroups W the same way).  Wherever a stage order reads  B W F_j B W  with j even, the first W
+    waits for the second:  B F_j B W W.  Keyed on the forward's microbatch, every stage pairs around the same
+    forwards, so no stage asks a neighbour for a tensor earlier than that neighbour, pairing the same way,
+    produces it; at zero transfer time the timing model's cost does not grow.  F, B and W each keep their
+    own sequence; at most one more W is pending at any time."""
+    src, out = list(ops), []
+    at = 0
+    while at < len(src):
+        five = src[at:at + 5]
+        if ([c for c, _ in five] == [B, W, F, B, W]) and five[2][1] % 2 == 0:
+            out.extend([five[0], five[2], five[3], five[1], five[4]])
+            at += 5
+        else:
+            out.append(src[at])
+            at += 1
+    return out
+
+
 def simulate(orders: Sequence[Sequence[Op]], T_F: float, T_B: float, T_W: float,
-             T_comm: float = 0.0, fused_backward: bool = False):
+             T_comm: float = 0.0, fused_backward: bool = False, T_W_next: float = None):
     """Start/end times of every pass of a p-stage pipeline.
 
     fused_backward=True models the traditional single backward function of 1F1B
     (Sec. 1: B at layer i-1 depends on W at layer i): the input gradient leaves
-    the stage only when the W glued to that B has finished."""
+    the stage only when the W glued to that B has finished.
+
+    T_W_next: duration of a W that directly follows another W on its stage (W passes run side by side share
+    the gradient's read and write); None: T_W."""
     p = len(orders)
     dur = {F: T_F, B: T_B, W: T_W}
     end: List[Dict[Op, float]] = [dict() for _ in range(p)]
@@ -138,7 +161,8 @@ def simulate(orders: Sequence[Sequence[Op]], T_F: float, T_B: float, T_W: float,
                 elif c == W and (B, k) not in end[i]:
                     raise AssertionError("W before B on one stage")
                 start[i][(c, k)] = ready
-                clock[i] = ready + dur[c]
+                follows_w = c == W and T_W_next is not None and ptr[i] > 0 and orders[i][ptr[i] - 1][0] == W
+                clock[i] = ready + (T_W_next if follows_w else dur[c])
                 end[i][(c, k)] = clock[i]
                 ptr[i] += 1
                 remaining -= 1

@@ -47,7 +47,7 @@ bool valid_orders(int p, int m, const zb_op* orders) {
 // fused_backward the input gradient leaves a stage only after the W of that microbatch (the single
 // backward function of 1F1B).  Returns false if the orders deadlock.
 bool run_timing(int p, int m, const zb_op* orders, const Times& t, bool fused_backward, std::vector<double>* first,
-                std::vector<double>* last) {
+                std::vector<double>* last, double t_w_next = -1.0) {
   const size_t n = (size_t)3 * m;
   std::vector<double> end((size_t)p * n, -1.0);  // [stage][pass][mb]
   std::vector<int> ptr(p, 0);
@@ -72,7 +72,10 @@ bool run_timing(int p, int m, const zb_op* orders, const Times& t, bool fused_ba
           if (e + t.comm > ready) ready = e + t.comm;
         }
         if (ptr[i] == 0) (*first)[i] = ready;
-        clock[i] = ready + t.of(op.pass);
+        // a W right behind another W of the same stage shares that one's gradient traffic (one launch)
+        const bool w_run = t_w_next >= 0 && op.pass == ZB_PASS_W && ptr[i] > 0 &&
+                           orders[(size_t)i * n + ptr[i] - 1].pass == ZB_PASS_W;
+        clock[i] = ready + (w_run ? t_w_next : t.of(op.pass));
         end[(size_t)i * n + (size_t)op.pass * m + op.mb] = clock[i];
         (*last)[i] = clock[i];
         ++ptr[i];
@@ -237,6 +240,19 @@ zb_status zb_simulate_pipeline(int32_t p, int32_t m, const zb_op* orders, const 
   const double c = span_cost(first, last);
   if (cost) *cost = c;
   if (bubble_rate) *bubble_rate = (c - m * (t.f + t.b + t.w)) / c;
+  if (stage_span)
+    for (int i = 0; i < p; ++i) stage_span[i] = last[i] - first[i];
+  return ZB_OK;
+}
+
+zb_status zb_simulate_pipeline_w_runs(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times,
+                                      double t_w_next, double* cost, double* stage_span) {
+  if (p < 1 || m < 1 || !orders || !valid_times(times) || !(t_w_next >= 0)) return ZB_EINVAL;
+  if (!valid_orders(p, m, orders)) return ZB_EORDER;
+  const Times t{times->t_f, times->t_b, times->t_w, times->t_comm};
+  std::vector<double> first, last;
+  if (!run_timing(p, m, orders, t, false, &first, &last, t_w_next)) return ZB_EORDER;
+  if (cost) *cost = span_cost(first, last);
   if (stage_span)
     for (int i = 0; i < p; ++i) stage_span[i] = last[i] - first[i];
   return ZB_OK;
@@ -428,6 +444,29 @@ zb_status zb_order_group_w(const zb_op* ops, int32_t n, int32_t group, zb_op* ou
     }
   }
   for (const zb_op& w : held) out[q++] = w;
+  return ZB_OK;
+}
+
+zb_status zb_order_pair_w(const zb_op* ops, int32_t n, zb_op* out) {
+  if (!ops || !out || n < 0) return ZB_EINVAL;
+  for (int32_t i = 0; i < n; ++i)
+    if (ops[i].pass < 0 || ops[i].pass > 2) return ZB_EINVAL;
+  auto is = [&](int32_t i, int pass) { return i < n && ops[i].pass == pass; };
+  int32_t q = 0;
+  for (int32_t i = 0; i < n;) {
+    // B W F_j B W with an even j: the first W joins the second, behind the second B
+    if (is(i, ZB_PASS_B) && is(i + 1, ZB_PASS_W) && is(i + 2, ZB_PASS_F) && is(i + 3, ZB_PASS_B) &&
+        is(i + 4, ZB_PASS_W) && ops[i + 2].mb % 2 == 0) {
+      out[q++] = ops[i];
+      out[q++] = ops[i + 2];
+      out[q++] = ops[i + 3];
+      out[q++] = ops[i + 1];
+      out[q++] = ops[i + 4];
+      i += 5;
+    } else {
+      out[q++] = ops[i++];
+    }
+  }
   return ZB_OK;
 }
 

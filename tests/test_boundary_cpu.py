@@ -106,3 +106,32 @@ def test_order_group_w_keeps_every_pass_and_the_w_sequence():
                 assert max_w <= base_w + group - 1 or max_w <= m
     buf = (zb.binding.zb_op * 4)()
     assert zb.lib.zb_order_group_w(buf, 3, 0, buf) == zb.EINVAL
+
+
+def test_order_pair_w_and_the_w_run_timing_model_match_the_oracle():
+    import random
+    import paper_2401_10241_amd as zb
+    from oracle.schedule import pair_w, simulate, stage_order
+    rng = random.Random(12)
+    for kind in ("1F1B", "H1", "H2"):
+        for p, m in ((4, 8), (16, 48), (8, 5), (3, 2), (32, 64)):
+            base = [zb.schedule_order(p, i, m, kind) for i in range(p)]
+            paired = [zb.order_pair_w(o) for o in base]
+            assert paired == [pair_w(stage_order(p, i, m, kind)) for i in range(p)]      # the oracle's rule, bit for bit
+            if kind == "1F1B":
+                continue
+            tf, tb, tw = (rng.uniform(0.5, 2.0) for _ in range(3))
+            tc = 0.05
+            for tw_next in (tw, 0.6 * tw, 0.0):
+                cost, spans = zb.simulate_pipeline_w_runs(paired, tf, tb, tw, tc, tw_next)
+                start, end = simulate(paired, tf, tb, tw, tc, T_W_next=tw_next)
+                want = [max(end[i].values()) - min(start[i].values()) for i in range(p)]
+                assert max(abs(a - b) for a, b in zip(spans, want)) < 1e-9 and abs(cost - max(want)) < 1e-9
+            # with t_w_next = t_w it is zb_simulate_pipeline's model
+            c0, _, _ = zb.simulate_pipeline(paired, tf, tb, tw, tc)
+            assert abs(c0 - zb.simulate_pipeline_w_runs(paired, tf, tb, tw, tc, tw)[0]) < 1e-12
+    buf = (zb.binding.zb_op * 4)()
+    assert zb.lib.zb_order_pair_w(None, 3, buf) == zb.EINVAL
+    t = zb.binding.zb_pass_times(1.0, 1.0, 1.0, 0.0)
+    import ctypes
+    assert zb.lib.zb_simulate_pipeline_w_runs(1, 1, buf, ctypes.byref(t), -1.0, None, None) == zb.EINVAL

@@ -160,6 +160,36 @@ def test_grouped_w_has_the_bits_of_one_by_one_w(shape):
         assert g.tobytes() == results[0].tobytes()
 
 
+def test_paired_w_order_has_the_bits_of_the_plain_order():
+    # the order with its steady-state W passes two at a time (zb_order_pair_w) through zb_run_order: the W of a
+    # parameter run in the same microbatch sequence, so every gradient, output and input gradient keeps every bit
+    import paper_2401_10241_amd as zb
+    m = 10
+    w = W("pairw", "bf16", 2, 256, 4, 1024, 128, 1, 4, 1, m, "H1", seed=27)
+    params = zb_inputs.stage_params(w)
+    plain = zb.schedule_order(w.p, w.stage, m, "H1")
+    paired = zb.order_pair_w(plain)
+    assert paired != plain and sorted(paired) == sorted(plain)
+    assert sum(1 for i in range(len(paired) - 1) if paired[i][0] == 2 and paired[i + 1][0] == 2) >= 3
+    results = []
+    for ops in (plain, paired):
+        pools = zb.order_stash_need(ops)
+        dev = make_device_stage(w, m, pools=pools)
+        dev.set_params(params)
+        dev.begin_iteration(0, m)
+        load_iteration(w, 0, m, dev)
+        dev.run_order(ops)
+        dev.synchronize()
+        results.append((dev.get_tensor(zb.T_FLAT_GRADS).copy(),
+                        [dev.get_tensor(zb.T_OUTPUT_DX, 0, k).copy() for k in range(m)]))
+        dev.close()
+    assert np.abs(results[0][0]).max() > 0
+    assert results[0][0].tobytes() == results[1][0].tobytes()
+    for a, b in zip(results[0][1], results[1][1]):
+        assert a.tobytes() == b.tobytes()
+    assert zb.order_stash_need(paired)[1] == zb.order_stash_need(plain)[1] + 1
+
+
 def test_fused_backward_has_the_bits_of_b_then_w():
     # the traditional single backward (layer by layer: input gradient, then that layer's parameter
     # gradients) against B then W of the split, bit for bit, and against the oracle
