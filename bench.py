@@ -87,9 +87,9 @@ def auto_schedule_report(zb, st, w, m, class_ms):
         orders = [zb.schedule_order(p, i, m, kind) for i in range(p)]
         rates["1F1B" if kind == "1F1B" else "ZB-" + kind] = round(
             zb.simulate_pipeline(orders, t_f, t_b, t_w, t_comm, fused_backward=(kind == "1F1B"))[1], 4)
-    # What holding W back into groups (zb_order_group_w, bench --w-group) would cost a real pipeline: the same pass
-    # times, every stage's ZB-H1 / ZB-H2 order regrouped.  On one GPU grouped W run faster (one read-modify-write of
-    # a gradient per group instead of per pass); in the pipeline the W passes no longer sit where the bubbles are.
+    # W passes of the steady state `grp` at a time (zb_order_group_w, bench --w-group), every stage regrouped the
+    # same way, at the SAME pass times: the price in bubbles alone (at most one t_comm per group); what it
+    # buys - grouped W run faster - is in `w_grouped` below.
     for grp in (2, 4):
         orders = [zb.order_group_w(zb.schedule_order(p, i, m, w.kind), grp) for i in range(p)]
         rates[f"ZB-{w.kind}, W in groups of {grp}"] = round(zb.simulate_pipeline(orders, t_f, t_b, t_w, t_comm)[1], 4)
@@ -109,18 +109,21 @@ def auto_schedule_report(zb, st, w, m, class_ms):
             "search_host_ms": round(search_ms, 2)}
 
 
-def paired_w_report(zb, st, w, m, kind, paired_ops, flops, auto, class_ms):
-    """The same iteration with the W passes of the order's steady state run two at a time (zb_order_pair_w;
-    Sec. 2: a W may run anywhere after its B, Appendix A): not the order `value` is measured on, reported
-    beside it.  Two W in one launch read and write every gradient once, so the W class gets faster on one
-    GPU; the p-stage timing model, fed with the measured time of a W that opens a run of W (t_w_first) and of
-    one that follows another (t_w_next), says what that does to a whole pipeline of such stages."""
+def grouped_w_report(zb, st, w, m, kind, group, flops, auto, class_ms):
+    """The same iteration with the W passes of the order's steady state run `group` at a time
+    (zb_order_group_w; Sec. 2: a W may run anywhere after its B, Appendix A): not the order `value` is
+    measured on, reported beside it.  W in one launch read and write every gradient once, so the W class gets
+    faster on one GPU; the p-stage timing model, fed with the measured time of a W that opens a run of W
+    (t_w_first) and of one that follows another (t_w_next), says what that does to a whole pipeline of such
+    stages, every stage regrouped the same way."""
     import torch
     import zb_inputs
+    base_ops = zb.schedule_order(w.p, w.stage, m, kind)
+    ops = zb.order_group_w(base_ops, group)
 
     def step(it):
         st.begin_iteration(it, m)
-        st.run_order(paired_ops)
+        st.run_order(ops)
         if w.optimizer:
             st.optimizer_step_validated(0.0, zb_inputs.rest_state(w, it), want_report=False)
 
@@ -138,29 +141,29 @@ def paired_w_report(zb, st, w, m, kind, paired_ops, flops, auto, class_ms):
     st.profile_enable(False)
     wg = pstats["gemm_wgrad"]
 
-    def runs_of_w(ops):
-        return sum(1 for i, (c, _) in enumerate(ops) if c == 2 and (i == 0 or ops[i - 1][0] != 2))
+    def runs_of_w(o):
+        return sum(1 for i, (c, _) in enumerate(o) if c == 2 and (i == 0 or o[i - 1][0] != 2))
 
-    base_ops = zb.schedule_order(w.p, w.stage, m, kind)
-    r0, r1 = runs_of_w(base_ops), runs_of_w(paired_ops)
+    r0, r1 = runs_of_w(base_ops), runs_of_w(ops)
     T0, T1 = class_ms["gemm_wgrad"] + class_ms.get("bias_grad_colsum", 0), wg["total_ms"]
+    rep = {"group": group, "value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+           "ms_per_step": round(ms, 3), "steps": n,
+           "gemm_wgrad": {"launches": wg["launches"], "total_ms": round(wg["total_ms"], 3),
+                          "tflops": round(wg["flops"] / wg["total_ms"] / 1e9, 1)},
+           "w_stash_slots": zb.order_stash_need(ops)[1], "w_stash_slots_plain_order": zb.order_stash_need(base_ops)[1]}
     # T = runs * t_first + (m - runs) * t_next for the two orders of this stage
     det = r0 * (m - r1) - r1 * (m - r0)
-    rep = {"value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(ms, 3),
-           "steps": n, "gemm_wgrad": {"launches": wg["launches"], "total_ms": round(wg["total_ms"], 3),
-                                      "tflops": round(wg["flops"] / wg["total_ms"] / 1e9, 1)},
-           "w_stash_slots": zb.order_stash_need(paired_ops)[1], "w_stash_slots_unpaired": zb.order_stash_need(base_ops)[1]}
     if det != 0:
         t_first = (T0 * (m - r1) - T1 * (m - r0)) / det
         t_next = (r0 * T1 - r1 * T0) / det
         t_f, t_b, t_comm = auto["t_f_ms"], auto["t_b_ms"], auto["t_comm_ms"]
         if t_first > 0 and t_next >= 0:
             base_all = [zb.schedule_order(w.p, i, m, kind) for i in range(w.p)]
-            pair_all = [zb.order_pair_w(o) for o in base_all]
+            grp_all = [zb.order_group_w(o, group) for o in base_all]
             c0 = zb.simulate_pipeline_w_runs(base_all, t_f, t_b, t_first, t_comm, t_next)[0]
-            c1 = zb.simulate_pipeline_w_runs(pair_all, t_f, t_b, t_first, t_comm, t_next)[0]
+            c1 = zb.simulate_pipeline_w_runs(grp_all, t_f, t_b, t_first, t_comm, t_next)[0]
             rep["pipeline_model"] = {"t_w_first_ms": round(t_first, 4), "t_w_next_ms": round(t_next, 4),
-                                     "iteration_ms": round(c0, 3), "iteration_ms_w_paired": round(c1, 3),
+                                     "iteration_ms": round(c0, 3), "iteration_ms_w_grouped": round(c1, 3),
                                      "speedup": round(c0 / c1, 4)}
     return rep
 
@@ -178,13 +181,10 @@ def main():
                          "(Sec. 6: the stage's layers as two chunks, 2m virtual microbatches; needs an even "
                          "number of layers)")
     ap.add_argument("--w-group", type=int, default=1,
-                    help="hold the order's W passes back until this many can run side by side (zb_order_group_w: "
-                         "same results bit for bit, group-1 more microbatches of W stash); 1 = the order as the "
-                         "paper gives it (default)")
-    ap.add_argument("--w-pair", action="store_true",
-                    help="run the order with the W passes of its steady state two at a time (zb_order_pair_w: same "
-                         "results bit for bit, one more microbatch of W stash); without this flag the default "
-                         "workload also measures that order, untimed for `value`, and reports it as `w_paired`")
+                    help="run the order with the W passes of its steady state this many at a time "
+                         "(zb_order_group_w: same results bit for bit, group-1 more microbatches of W stash); 1 = the "
+                         "order as the paper gives it (default; the default workload then also measures groups of 2 "
+                         "and 4, untimed for `value`, and reports them as `w_grouped`)")
     ap.add_argument("--role", default="middle", choices=["middle", "first", "last"],
                     help="first / last stage of the pipeline (Sec. 5.1): one transformer layer fewer than the "
                          "workload's middle stage, plus the embedding lookup (first) or the final LayerNorm, head "
@@ -228,17 +228,14 @@ def main():
     elif args.w_group > 1:
         v_ops = zb.order_group_w(zb.schedule_order(w.p, w.stage, m, kind), args.w_group)
         pb, pw, fl = zb.order_stash_need(v_ops)
-    elif args.w_pair:
-        v_ops = zb.order_pair_w(zb.schedule_order(w.p, w.stage, m, kind))
-        pb, pw, fl = zb.order_stash_need(v_ops)
     else:
         pb, pw, fl = zb.schedule_stash_need(w.p, w.stage, m, kind)
-    explicit = zbv or args.w_group > 1 or args.w_pair
-    # the default run also measures the paired-W order afterwards, on the same stage: give the pools its slots
-    also_paired = not explicit and args.order == "workload" and args.role == "middle" and not args.no_profile and not args.m
-    if also_paired:
-        paired_ops = zb.order_pair_w(zb.schedule_order(w.p, w.stage, m, kind))
-        pb2, pw2, fl2 = zb.order_stash_need(paired_ops)
+    explicit = zbv or args.w_group > 1
+    # the default run also measures the order with grouped W afterwards, on the same stage: give the pools its slots
+    also_grouped = (2, 4) if (not explicit and args.order == "workload" and args.role == "middle"
+                              and not args.no_profile and not args.m) else ()
+    for g in also_grouped:
+        pb2, pw2, fl2 = zb.order_stash_need(zb.order_group_w(zb.schedule_order(w.p, w.stage, m, kind), g))
         pb, pw, fl = max(pb, pb2), max(pw, pw2), max(fl, fl2)
     m_run = 2 * m if zbv else m          # virtual microbatches (chunk * m + microbatch) under ZB-V
     st = zb.Stage(role=args.role, vocab=vocab, fuse_bw=(args.order == "1F1B-fused"), chunks=(2 if zbv else 1), layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, mb_size=w.mb_size,
@@ -302,8 +299,7 @@ def main():
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "config": {"workload": f"{w.name}: " + (f"{args.role} " if args.role != "middle" else "") + f"stage {w.stage} of p={w.p}, "
                                + (f"ZB-{w.kind}" if args.order == "workload" else args.order)
-                               + (f" order with W held back into groups of {args.w_group}" if args.w_group > 1
-                                  else " order with steady-state W passes two at a time" if args.w_pair
+                               + (f" order with steady-state W passes {args.w_group} at a time" if args.w_group > 1
                                   else " order") + f", m={m}, {w.layers} GPT "
                                f"decoder layers h={w.hidden} a={w.heads} ffn={w.ffn} seq={w.seq} b={w.mb_size}"
                                + (", validated AdamW step" if w.optimizer else ""),
@@ -377,9 +373,9 @@ def main():
             out["optimizer_forced_rollback"] = fr
         out["kernels"] = kern
         out["auto_schedule"] = auto_schedule_report(zb, st, w, m, {r["name"]: r["total_ms"] for r in stats})
-        if also_paired:
-            out["w_paired"] = paired_w_report(zb, st, w, m, kind, paired_ops, flops, out["auto_schedule"],
-                                              {r["name"]: r["total_ms"] for r in stats})
+        if also_grouped:
+            out["w_grouped"] = [grouped_w_report(zb, st, w, m, kind, g, flops, out["auto_schedule"],
+                                                 {r["name"]: r["total_ms"] for r in stats}) for g in also_grouped]
     st.close()
     del st
     torch.cuda.empty_cache()

@@ -244,27 +244,21 @@ zb_status zb_schedule_order_v(int32_t p, int32_t m, zb_op* orders);
 zb_status zb_simulate_pipeline_v(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times, double* cost,
                                  double* bubble_rate, double* stage_span);
 
-/* The same stage order with its W passes held back until `group` of them can run side by side (Sec. 2: a W
- * may run anywhere after its B; Appendix A regroups deferred W the same way): every F and B keeps its place,
- * a W moves behind later F / B passes until group W are waiting, the last ones run at the end.  W stay in
- * their original sequence, so accumulated gradients keep every bit (see zb_backward_weight_group); the price
- * is group - 1 more microbatches of W stash (zb_order_stash_need / zb_order_memory_peak on the result) and
- * whatever the p-stage timing model says about the bubbles.  ops and out: n entries each (host), group >= 1. */
+/* The same stage order with the W passes of its 1F1B-shaped steady state run `group` at a time (Sec. 2: a W
+ * may run anywhere after its B; Appendix A regroups W the same way): wherever the order reads
+ * B W F_j B W F B W ... B W  (group times B W, a forward between each two) with the first forward's
+ * microbatch j a multiple of group, the W wait for the last of them:  B F_j B F ... B W W ... W.  Keyed on the
+ * forward's microbatch, all stages of a pipeline group around the same forwards, so no stage wants a tensor
+ * earlier than its neighbour, grouping the same way, sends it: at zero transfer time the timing model's cost
+ * does not grow (at most one t_comm per group otherwise), while W side by side read and write every gradient
+ * once (zb_backward_weight_group; zb_run_order runs consecutive W that way).  F, B and W each keep their
+ * sequence, so results keep every bit; group - 1 more W stashes are pending at the peak
+ * (zb_order_stash_need / zb_order_memory_peak on the result).  ops and out: n entries each (host), group >= 1
+ * (1: a copy). */
 zb_status zb_order_group_w(const zb_op* ops, int32_t n, int32_t group, zb_op* out);
 
-/* The same stage order with the W passes of its 1F1B-shaped steady state run two at a time (Sec. 2: a W may
- * run anywhere after its B; Appendix A): wherever the order reads  B W F_j B W  with an even microbatch j of
- * the forward, the first W waits for the second,  B F_j B W W.  Keyed on the forward's microbatch, all
- * stages of a pipeline pair around the same forwards, so no stage wants a tensor earlier than its neighbour,
- * pairing the same way, sends it: at zero transfer time the timing model's cost does not grow (at most one
- * t_comm per pair otherwise), while two W side by side read and write every gradient once
- * (zb_backward_weight_group; zb_run_order runs consecutive W that way).  F, B and W each keep their
- * sequence, so results keep every bit; one more W stash is pending at the peak (zb_order_stash_need on the
- * result).  ops and out: n entries each (host). */
-zb_status zb_order_pair_w(const zb_op* ops, int32_t n, zb_op* out);
-
 /* zb_simulate_pipeline's model with one more time: a W that directly follows another W on its stage takes
- * t_w_next >= 0 (measured: the second W of a two-W launch).  No fused backward; *cost = largest stage span. */
+ * t_w_next >= 0 (measured: the later W of a grouped launch).  No fused backward; *cost = largest stage span. */
 zb_status zb_simulate_pipeline_w_runs(int32_t p, int32_t m, const zb_op* orders, const zb_pass_times* times,
                                       double t_w_next, double* cost, double* stage_span);
 

@@ -103,20 +103,26 @@ def stash_profile(ops: Sequence[Op], M_B: float = 1.0, M_W: float = 0.0):
     return peak, at[0], at[1], max_b, max_w
 
 
-def pair_w(ops: Sequence[Op]) -> List[Op]:
-    """W passes of the 1F1B-shaped steady state run two at a time (Sec. 2: a W may run anywhere after its B;
-    Appendix A regroups W the same way).  Wherever a stage order reads  B W F_j B W  with j even, the first W
-    waits for the second:  B F_j B W W.  Keyed on the forward's microbatch, every stage pairs around the same
-    forwards, so no stage asks a neighbour for a tensor earlier than that neighbour, pairing the same way,
-    produces it; at zero transfer time the timing model's cost does not grow.  F, B and W each keep their
-    own sequence; at most one more W is pending at any time."""
+def group_w(ops: Sequence[Op], g: int) -> List[Op]:
+    """W passes of the 1F1B-shaped steady state run g at a time (Sec. 2: a W may run anywhere after its B;
+    Appendix A regroups W the same way).  Wherever a stage order reads  B W F_j B W F B W ... B W  (g times
+    B W, forwards between) with j a multiple of g, the W wait for the last of them:  B F_j B F ... B W W ... W.
+    Keyed on the forward's microbatch, every stage groups around the same forwards, so no stage asks a
+    neighbour for a tensor earlier than that neighbour, grouping the same way, produces it; at zero transfer
+    time the timing model's cost does not grow.  F, B and W each keep their own sequence; at most g - 1 more
+    W are pending at any time."""
+    if g < 1:
+        raise ValueError("group size must be at least 1")
     src, out = list(ops), []
+    span = 3 * g - 1
+    shape = [(B, W, F)[q % 3] for q in range(span)]
     at = 0
     while at < len(src):
-        five = src[at:at + 5]
-        if ([c for c, _ in five] == [B, W, F, B, W]) and five[2][1] % 2 == 0:
-            out.extend([five[0], five[2], five[3], five[1], five[4]])
-            at += 5
+        window = src[at:at + span]
+        if g > 1 and [c for c, _ in window] == shape and window[2][1] % g == 0:
+            out.extend(op for op in window if op[0] != W)
+            out.extend(op for op in window if op[0] == W)
+            at += span
         else:
             out.append(src[at])
             at += 1

@@ -110,7 +110,6 @@ _sig = {
                                 _P(C.c_double), _P(C.c_double), _P(C.c_int32), _P(C.c_int32)],
     "zb_order_memory_peak": [_P(zb_op), C.c_int32, C.c_double, C.c_double, _P(C.c_double)],
     "zb_order_group_w": [_P(zb_op), C.c_int32, C.c_int32, _P(zb_op)],
-    "zb_order_pair_w": [_P(zb_op), C.c_int32, _P(zb_op)],
     "zb_simulate_pipeline_w_runs": [C.c_int32, C.c_int32, _P(zb_op), _P(zb_pass_times), C.c_double, _P(C.c_double),
                                     _P(C.c_double)],
     "zb_schedule_order_v": [C.c_int32, C.c_int32, _P(zb_op)],
@@ -254,15 +253,6 @@ def simulate_pipeline_v(orders, m: int, t_f: float, t_b: float, t_w: float,
     return cost.value, rate.value, list(spans)
 
 
-def order_pair_w(ops) -> List[Tuple[int, int]]:
-    """zb_order_pair_w: the order with the W passes of its steady state run two at a time."""
-    out = (zb_op * max(len(ops), 1))()
-    rc = lib.zb_order_pair_w(_pack_order(ops), len(ops), out)
-    if rc != OK:
-        raise ZbError(rc, "zb_order_pair_w")
-    return [(out[i].pass_, out[i].mb) for i in range(len(ops))]
-
-
 def simulate_pipeline_w_runs(orders, t_f: float, t_b: float, t_w: float, t_comm: float,
                              t_w_next: float) -> Tuple[float, List[float]]:
     """zb_simulate_pipeline_w_runs: (cost, per-stage spans); a W right behind a W takes t_w_next."""
@@ -277,7 +267,7 @@ def simulate_pipeline_w_runs(orders, t_f: float, t_b: float, t_w: float, t_comm:
 
 
 def order_group_w(ops, group: int) -> List[Tuple[int, int]]:
-    """zb_order_group_w: the order with its W passes held back into groups of `group`."""
+    """zb_order_group_w: the order with the W passes of its steady state run `group` at a time."""
     out = (zb_op * max(len(ops), 1))()
     rc = lib.zb_order_group_w(_pack_order(ops), len(ops), group, out)
     if rc != OK:

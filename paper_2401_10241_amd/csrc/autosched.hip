@@ -432,37 +432,25 @@ zb_status zb_simulate_pipeline_v(int32_t p, int32_t m, const zb_op* orders, cons
 
 zb_status zb_order_group_w(const zb_op* ops, int32_t n, int32_t group, zb_op* out) {
   if (!ops || !out || n < 0 || group < 1) return ZB_EINVAL;
-  std::vector<zb_op> held;
-  int32_t q = 0;
-  for (int32_t i = 0; i < n; ++i) {
-    if (ops[i].pass < 0 || ops[i].pass > 2) return ZB_EINVAL;
-    if (ops[i].pass != ZB_PASS_W) { out[q++] = ops[i]; continue; }
-    held.push_back(ops[i]);
-    if ((int32_t)held.size() == group) {
-      for (const zb_op& w : held) out[q++] = w;
-      held.clear();
-    }
-  }
-  for (const zb_op& w : held) out[q++] = w;
-  return ZB_OK;
-}
-
-zb_status zb_order_pair_w(const zb_op* ops, int32_t n, zb_op* out) {
-  if (!ops || !out || n < 0) return ZB_EINVAL;
   for (int32_t i = 0; i < n; ++i)
     if (ops[i].pass < 0 || ops[i].pass > 2) return ZB_EINVAL;
-  auto is = [&](int32_t i, int pass) { return i < n && ops[i].pass == pass; };
+  // B W F_j B W F ... B W: `group` times B W with a forward between each two, j a multiple of group
+  const int64_t span = 3 * (int64_t)group - 1;
+  auto group_starts_at = [&](int32_t i) {
+    if (group < 2 || i + span > n || ops[i + 2].mb % group != 0) return false;
+    for (int64_t d = 0; d < span; ++d) {
+      const int want = d % 3 == 0 ? ZB_PASS_B : d % 3 == 1 ? ZB_PASS_W : ZB_PASS_F;
+      if (ops[i + d].pass != want) return false;
+    }
+    return true;
+  };
   int32_t q = 0;
   for (int32_t i = 0; i < n;) {
-    // B W F_j B W with an even j: the first W joins the second, behind the second B
-    if (is(i, ZB_PASS_B) && is(i + 1, ZB_PASS_W) && is(i + 2, ZB_PASS_F) && is(i + 3, ZB_PASS_B) &&
-        is(i + 4, ZB_PASS_W) && ops[i + 2].mb % 2 == 0) {
-      out[q++] = ops[i];
-      out[q++] = ops[i + 2];
-      out[q++] = ops[i + 3];
-      out[q++] = ops[i + 1];
-      out[q++] = ops[i + 4];
-      i += 5;
+    if (group_starts_at(i)) {  // the forwards and backwards first, then the W side by side
+      for (int64_t d = 0; d < span; ++d)
+        if (d % 3 != 1) out[q++] = ops[i + d];
+      for (int64_t d = 1; d < span; d += 3) out[q++] = ops[i + d];
+      i += (int32_t)span;
     } else {
       out[q++] = ops[i++];
     }

@@ -81,57 +81,41 @@ def test_stage_refuses_to_run_without_a_gpu():
                  max_pending_w=1, max_inflight=1)
 
 
-def test_order_group_w_keeps_every_pass_and_the_w_sequence():
-    import paper_2401_10241_amd as zb
-    from oracle.schedule import check_order, stash_profile
-    for kind in ("1F1B", "H1", "H2"):
-        for p, sigma, m in ((4, 1, 8), (16, 8, 48), (8, 7, 5), (3, 0, 2)):
-            base = zb.schedule_order(p, sigma, m, kind)
-            assert zb.order_group_w(base, 1) == base
-            for group in (2, 3, 4, 64):
-                got = zb.order_group_w(base, group)
-                check_order(got, m)                                      # F_k before B_k before W_k, each once
-                assert [op for op in got if op[0] != 2] == [op for op in base if op[0] != 2]   # F and B keep their places
-                assert [k for c, k in got if c == 2] == [k for c, k in base if c == 2]         # W in their sequence
-                runs, cur = [], 0
-                for c, _ in got:                                          # lengths of the runs of consecutive W
-                    if c == 2:
-                        cur += 1
-                    elif cur:
-                        runs.append(cur)
-                        cur = 0
-                assert all(r >= min(group, m) for r in runs)             # only the last run (at the end) may be shorter
-                _, _, _, _, max_w = stash_profile(got)
-                _, _, _, _, base_w = stash_profile(base)
-                assert max_w <= base_w + group - 1 or max_w <= m
-    buf = (zb.binding.zb_op * 4)()
-    assert zb.lib.zb_order_group_w(buf, 3, 0, buf) == zb.EINVAL
-
-
-def test_order_pair_w_and_the_w_run_timing_model_match_the_oracle():
+def test_order_group_w_and_the_w_run_timing_model_match_the_oracle():
+    import ctypes
     import random
     import paper_2401_10241_amd as zb
-    from oracle.schedule import pair_w, simulate, stage_order
+    from oracle.schedule import check_order, group_w, simulate, stage_order, stash_profile
     rng = random.Random(12)
     for kind in ("1F1B", "H1", "H2"):
         for p, m in ((4, 8), (16, 48), (8, 5), (3, 2), (32, 64)):
             base = [zb.schedule_order(p, i, m, kind) for i in range(p)]
-            paired = [zb.order_pair_w(o) for o in base]
-            assert paired == [pair_w(stage_order(p, i, m, kind)) for i in range(p)]      # the oracle's rule, bit for bit
-            if kind == "1F1B":
-                continue
-            tf, tb, tw = (rng.uniform(0.5, 2.0) for _ in range(3))
-            tc = 0.05
-            for tw_next in (tw, 0.6 * tw, 0.0):
-                cost, spans = zb.simulate_pipeline_w_runs(paired, tf, tb, tw, tc, tw_next)
-                start, end = simulate(paired, tf, tb, tw, tc, T_W_next=tw_next)
-                want = [max(end[i].values()) - min(start[i].values()) for i in range(p)]
-                assert max(abs(a - b) for a, b in zip(spans, want)) < 1e-9 and abs(cost - max(want)) < 1e-9
-            # with t_w_next = t_w it is zb_simulate_pipeline's model
-            c0, _, _ = zb.simulate_pipeline(paired, tf, tb, tw, tc)
-            assert abs(c0 - zb.simulate_pipeline_w_runs(paired, tf, tb, tw, tc, tw)[0]) < 1e-12
+            assert [zb.order_group_w(o, 1) for o in base] == base
+            for group in (2, 3, 4, 64):
+                grouped = [zb.order_group_w(o, group) for o in base]
+                assert grouped == [group_w(stage_order(p, i, m, kind), group) for i in range(p)]   # the oracle's rule, bit for bit
+                for o, b in zip(grouped, base):
+                    check_order(o, m)                                              # F_k before B_k before W_k, each once
+                    assert [op for op in o if op[0] != 2] == [op for op in b if op[0] != 2]   # F and B keep their sequence
+                    assert [k for c, k in o if c == 2] == [k for c, k in b if c == 2]         # W in their sequence
+                    assert stash_profile(o)[4] <= stash_profile(b)[4] + group - 1
+                if kind == "1F1B" or group > 4:
+                    continue
+                tf, tb, tw = (rng.uniform(0.5, 2.0) for _ in range(3))
+                tc = 0.05
+                for tw_next in (tw, 0.6 * tw, 0.0):
+                    cost, spans = zb.simulate_pipeline_w_runs(grouped, tf, tb, tw, tc, tw_next)
+                    start, end = simulate(grouped, tf, tb, tw, tc, T_W_next=tw_next)
+                    want = [max(end[i].values()) - min(start[i].values()) for i in range(p)]
+                    assert max(abs(a - b) for a, b in zip(spans, want)) < 1e-9 and abs(cost - max(want)) < 1e-9
+                # with t_w_next = t_w it is zb_simulate_pipeline's model
+                c0, _, _ = zb.simulate_pipeline(grouped, tf, tb, tw, tc)
+                assert abs(c0 - zb.simulate_pipeline_w_runs(grouped, tf, tb, tw, tc, tw)[0]) < 1e-12
+    # the c4 stage: its steady state gives 16 runs of two W, the tail one longer run
+    o = zb.order_group_w(zb.schedule_order(16, 8, 48, "H1"), 2)
+    assert sum(1 for i in range(len(o) - 1) if o[i][0] == 2 and o[i + 1][0] == 2 and (i == 0 or o[i - 1][0] != 2)) == 17
     buf = (zb.binding.zb_op * 4)()
-    assert zb.lib.zb_order_pair_w(None, 3, buf) == zb.EINVAL
+    assert zb.lib.zb_order_group_w(buf, 3, 0, buf) == zb.EINVAL
+    assert zb.lib.zb_order_group_w(None, 3, 2, buf) == zb.EINVAL
     t = zb.binding.zb_pass_times(1.0, 1.0, 1.0, 0.0)
-    import ctypes
     assert zb.lib.zb_simulate_pipeline_w_runs(1, 1, buf, ctypes.byref(t), -1.0, None, None) == zb.EINVAL

@@ -160,15 +160,16 @@ def test_grouped_w_has_the_bits_of_one_by_one_w(shape):
         assert g.tobytes() == results[0].tobytes()
 
 
-def test_paired_w_order_has_the_bits_of_the_plain_order():
-    # the order with its steady-state W passes two at a time (zb_order_pair_w) through zb_run_order: the W of a
-    # parameter run in the same microbatch sequence, so every gradient, output and input gradient keeps every bit
+@pytest.mark.parametrize("group", [2, 3])
+def test_w_grouped_order_has_the_bits_of_the_plain_order(group):
+    # the order with its steady-state W passes `group` at a time (zb_order_group_w) through zb_run_order: the W of
+    # a parameter run in the same microbatch sequence, so every gradient and input gradient keeps every bit
     import paper_2401_10241_amd as zb
-    m = 10
+    m = 12
     w = W("pairw", "bf16", 2, 256, 4, 1024, 128, 1, 4, 1, m, "H1", seed=27)
     params = zb_inputs.stage_params(w)
     plain = zb.schedule_order(w.p, w.stage, m, "H1")
-    paired = zb.order_pair_w(plain)
+    paired = zb.order_group_w(plain, group)
     assert paired != plain and sorted(paired) == sorted(plain)
     assert sum(1 for i in range(len(paired) - 1) if paired[i][0] == 2 and paired[i + 1][0] == 2) >= 3
     results = []
@@ -187,7 +188,7 @@ def test_paired_w_order_has_the_bits_of_the_plain_order():
     assert results[0][0].tobytes() == results[1][0].tobytes()
     for a, b in zip(results[0][1], results[1][1]):
         assert a.tobytes() == b.tobytes()
-    assert zb.order_stash_need(paired)[1] == zb.order_stash_need(plain)[1] + 1
+    assert zb.order_stash_need(paired)[1] == zb.order_stash_need(plain)[1] + group - 1
 
 
 def test_fused_backward_has_the_bits_of_b_then_w():

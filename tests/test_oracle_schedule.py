@@ -7,7 +7,7 @@ import random
 import pytest
 
 from oracle.schedule import (stage_order, check_order, stash_profile, pipeline_cost, bubble_rate,
-                             simulate, pair_w, F, B, W)
+                             simulate, group_w, F, B, W)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "bubble_rates.txt")
 
@@ -121,7 +121,7 @@ def test_cross_stage_dependencies_hold_in_simulation():
             assert start[i][(B, k)] >= end[i][(F, k)] and start[i][(W, k)] >= end[i][(B, k)]
 
 
-# ---- W passes two at a time (Sec. 2: W anywhere after its B; Appendix A regroups W) ----------------------
+# ---- W passes g at a time (Sec. 2: W anywhere after its B; Appendix A regroups W) ------------------------
 
 def _span_cost(orders, tf, tb, tw, tc, tw_next=None):
     start, end = simulate(orders, tf, tb, tw, tc, T_W_next=tw_next)
@@ -129,14 +129,15 @@ def _span_cost(orders, tf, tb, tw, tc, tw_next=None):
 
 
 @pytest.mark.parametrize("kind", ["1F1B", "H1", "H2"])
-def test_paired_w_keeps_every_sequence_and_needs_one_more_pending_w(kind):
+def test_grouped_w_keeps_every_sequence_and_needs_g_minus_1_more_pending_w(kind):
     rng = random.Random(5)
-    for _ in range(40):
+    for _ in range(60):
         p = rng.randint(1, 12)
         m = rng.randint(1, 40)
         sigma = rng.randrange(p)
+        g = rng.randint(1, 5)
         ops = stage_order(p, sigma, m, kind)
-        out = pair_w(ops)
+        out = group_w(ops, g)
         check_order(out, m)
         for c in (F, B, W):   # each kind of pass keeps its own sequence: the gradient sums keep every bit
             assert [k for cc, k in out if cc == c] == [k for cc, k in ops if cc == c]
@@ -144,42 +145,52 @@ def test_paired_w_keeps_every_sequence_and_needs_one_more_pending_w(kind):
         assert [(cc, k) for cc, k in out if cc != W] == [(cc, k) for cc, k in ops if cc != W]
         _, _, _, _, max_w0 = stash_profile(ops)
         _, _, _, _, max_w1 = stash_profile(out)
-        assert max_w0 <= max_w1 <= max_w0 + 1
-        assert pair_w(out) == out or kind == "1F1B"   # nothing left to pair in a paired ZB order
+        assert max_w0 <= max_w1 <= max_w0 + g - 1
+        if g == 1:
+            assert out == ops
 
 
-def test_paired_w_by_hand():
+def test_grouped_w_by_hand():
     # p = 2, stage 1 (the last), m = 4, ZB-H1: F0 B0 F1 B1 W0 F2 B2 W1 F3 B3 W2 W3
     ops = stage_order(2, 1, 4, "H1")
     assert ops == [(F, 0), (B, 0), (F, 1), (B, 1), (W, 0), (F, 2), (B, 2), (W, 1), (F, 3), (B, 3), (W, 2), (W, 3)]
     # the only  B W F_j B W  with j even is  B1 W0 F2 B2 W1
-    assert pair_w(ops) == [(F, 0), (B, 0), (F, 1), (B, 1), (F, 2), (B, 2), (W, 0), (W, 1), (F, 3), (B, 3), (W, 2), (W, 3)]
+    assert group_w(ops, 2) == [(F, 0), (B, 0), (F, 1), (B, 1), (F, 2), (B, 2), (W, 0), (W, 1), (F, 3), (B, 3), (W, 2), (W, 3)]
+    # groups of three: B W F_j B W F B W needs j % 3 == 0:  B2 W1 F3 B3 W2 is too short, nothing moves
+    assert group_w(ops, 3) == ops
+    # the middle of a long ZB-H1 order in groups of three
+    mid = group_w(stage_order(4, 2, 12, "H1"), 3)
+    text = " ".join("FBW"[c] + str(k) for c, k in mid)
+    assert text == ("F0 F1 B0 F2 B1 F3 B2 W0 F4 B3 W1 F5 B4 F6 B5 F7 B6 W2 W3 W4 F8 B7 F9 B8 F10 B9 W5 W6 W7 "
+                    "F11 B10 W8 B11 W9 W10 W11")
 
 
-def test_paired_w_costs_nothing_without_transfer_time():
-    """Pairing is keyed on the forward's microbatch, so all stages shift the same forwards and backwards: with
+def test_grouped_w_costs_nothing_without_transfer_time():
+    """Grouping is keyed on the forward's microbatch, so all stages shift the same forwards and backwards: with
     T_comm = 0 the pipeline is never slower than with the W one by one, whatever the pass times."""
     rng = random.Random(9)
     for _ in range(25):
         p = rng.choice([2, 3, 4, 8, 16])
         m = rng.randint(p, 4 * p + 3)
+        g = rng.randint(2, 4)
         tf, tb, tw = (rng.uniform(0.5, 2.0) for _ in range(3))
         for kind in ("H1", "H2"):
             base = [stage_order(p, i, m, kind) for i in range(p)]
-            paired = [pair_w(o) for o in base]
-            assert _span_cost(paired, tf, tb, tw, 0.0) <= _span_cost(base, tf, tb, tw, 0.0) + 1e-9
+            grouped = [group_w(o, g) for o in base]
+            assert _span_cost(grouped, tf, tb, tw, 0.0) <= _span_cost(base, tf, tb, tw, 0.0) + 1e-9
 
 
-def test_shorter_second_w_shortens_the_pipeline():
+def test_shorter_following_w_shortens_the_pipeline():
     p, m = 16, 48
     tf, tb, tw, tc = 2.10, 2.41, 2.44, 0.07
     base = [stage_order(p, i, m, "H1") for i in range(p)]
-    paired = [pair_w(o) for o in base]
     c0 = _span_cost(base, tf, tb, tw, tc)
     assert abs(c0 - pipeline_cost(p, m, "H1", tf, tb, tw, tc)) < 1e-9
-    c1 = _span_cost(paired, tf, tb, tw, tc)
-    assert c0 <= c1 <= c0 + m * tc          # with transfer time: at most one T_comm per pair
-    c2 = _span_cost(paired, tf, tb, tw, tc, tw_next=0.7 * tw)
-    assert c2 < c0                           # a second W at 70 % of the time: a shorter iteration
-    # T_W_next = T_W is the plain model
-    assert abs(_span_cost(paired, tf, tb, tw, tc, tw_next=tw) - c1) < 1e-12
+    for g in (2, 4):
+        grouped = [group_w(o, g) for o in base]
+        c1 = _span_cost(grouped, tf, tb, tw, tc)
+        assert c0 <= c1 <= c0 + m * tc          # with transfer time: at most one T_comm per group
+        c2 = _span_cost(grouped, tf, tb, tw, tc, tw_next=0.7 * tw)
+        assert c2 < c0                           # following W at 70 % of the time: a shorter iteration
+        # T_W_next = T_W is the plain model
+        assert abs(_span_cost(grouped, tf, tb, tw, tc, tw_next=tw) - c1) < 1e-12
