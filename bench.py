@@ -189,6 +189,9 @@ def main():
                     help="first / last stage of the pipeline (Sec. 5.1): one transformer layer fewer than the "
                          "workload's middle stage, plus the embedding lookup (first) or the final LayerNorm, head "
                          "and cross-entropy loss (last), vocabulary 50432; order of stage 0 / stage p-1")
+    ap.add_argument("--no-w-grouped", action="store_true",
+                    help="leave out the extra steps in the order with grouped W (so that a kernel trace of the run "
+                         "holds the paper's order only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -233,7 +236,7 @@ def main():
     explicit = zbv or args.w_group > 1
     # the default run also measures the order with grouped W afterwards, on the same stage: give the pools its slots
     also_grouped = (2, 4) if (not explicit and args.order == "workload" and args.role == "middle"
-                              and not args.no_profile and not args.m) else ()
+                              and not args.no_profile and not args.m and not args.no_w_grouped) else ()
     for g in also_grouped:
         pb2, pw2, fl2 = zb.order_stash_need(zb.order_group_w(zb.schedule_order(w.p, w.stage, m, kind), g))
         pb, pw, fl = max(pb, pb2), max(pw, pw2), max(fl, fl2)
