@@ -99,7 +99,11 @@ def test_end_stage_parity(case):
     role, dtype, layers, hidden, heads, ffn, seq, b, vocab, m = case
     p = 4
     sigma = 0 if role == "first" else p - 1
-    w = W("end", dtype, layers, hidden, heads, ffn, seq, b, p, sigma, m, "H1", seed=61 + hidden, lr=1e-3)
+    # lr as in the paper's workloads.  The first Adam step moves every weight by lr * sign(g); where g is
+    # smaller than the rounding noise the device and the oracle may disagree on the sign, and the second
+    # iteration below then runs on weights that differ by 2 lr in those entries - at lr = 1e-3 (5 % of a
+    # weight's standard deviation) that, not the kernels, decided the largest element errors of iteration 2
+    w = W("end", dtype, layers, hidden, heads, ffn, seq, b, p, sigma, m, "H1", seed=61 + hidden, lr=1e-4)
     dev, orc = build(w, role, vocab)
     dev.begin_iteration(0, m)
     orc.begin_iteration(m)
