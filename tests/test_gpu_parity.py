@@ -62,10 +62,13 @@ def test_head_dim_96_and_single_microbatch():
 
 
 @pytest.mark.parametrize("d,heads,seq,b", [(128, 2, 256, 1), (96, 2, 256, 1), (64, 4, 384, 2), (128, 1, 512, 1),
-                                           (128, 8, 384, 2)])
+                                           (128, 8, 384, 2), (128, 1, 128, 3), (128, 1, 640, 1), (96, 1, 1152, 1),
+                                           (128, 2, 2048, 1)])
 def test_mfma_attention_shapes(d, heads, seq, b):
     # several query/key tiles per head, diagonal tiles, every supported head size, two sequences per microbatch;
-    # the last case has a multiple of 8 heads (backward workgroups ordered per XCD) and an odd number of blocks
+    # (128, 8, 384, 2) has a multiple of 8 heads (backward workgroups ordered per XCD) and an odd number of blocks;
+    # then a single row block (each of the forward's two wave groups gets one key tile), 5 and 9 blocks, and 16
+    # blocks of 2048 tokens (twice the workloads' sequence: 32 key tiles for the last row block)
     h = d * heads
     w = W(f"attn_d{d}_s{seq}", "bf16", 1, h, heads, 4 * h, seq, b, 2, 0, 2, "H1", seed=40 + d)
     run_and_compare(w)
