@@ -146,7 +146,7 @@ def test_end_stage_gradients_are_bitwise_identical_across_orders_and_groupings(r
     vocab = 512
     results = []
     flat = [(0, k) for k in range(m)] + [(1, k) for k in range(m)] + [(2, k) for k in range(m)]
-    for mode in ("H1 grouped", "H1 one by one", "flat", "1F1B fused", "W held back in groups of 3"):
+    for mode in ("H1 grouped", "H1 one by one", "flat", "1F1B fused", "W in aligned groups of 2"):
         dev, _ = build(w, role, vocab, pools=(m, m, m), **({"fuse_bw": True} if mode == "1F1B fused" else {}))
         dev.begin_iteration(0, m)
         load(w, role, vocab, 0, m, dev)
@@ -154,8 +154,11 @@ def test_end_stage_gradients_are_bitwise_identical_across_orders_and_groupings(r
             dev.run_schedule(p, sigma, m, "H1")
         elif mode == "1F1B fused":
             dev.run_schedule(p, sigma, m, "1F1B")
-        elif mode.startswith("W held"):
-            dev.run_order(zb.order_group_w(zb.schedule_order(p, sigma, m, "H1"), 3))
+        elif mode.startswith("W in aligned"):
+            plain = zb.schedule_order(p, sigma, m, "H1")
+            grouped = zb.order_group_w(plain, 2)
+            assert grouped != plain
+            dev.run_order(grouped)
         else:
             for c, k in (flat if mode == "flat" else zb.schedule_order(p, sigma, m, "H1")):
                 (dev.forward, dev.backward_input, dev.backward_weight)[c](k)
