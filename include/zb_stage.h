@@ -303,7 +303,7 @@ zb_status zb_optimizer_step_validated(zb_stage* st, const zb_global_state* gs, z
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc): the first step of zb_optimizer_step_validated, the squared norm and the
  * non-finite flag of a gradient vector, with the partial sums of its reduction levels in a fixed array
- * inside the library (about 12.6 MB per GPU, held until the process ends) instead of a stage's arena.
+ * inside the library (about 3.2 MB per GPU, held until the process ends) instead of a stage's arena.
  *   grads          device, n floats, 16-byte aligned; n > 0, n % 4 == 0, n <= ZB_GRAD_NORM_STATIC_MAX_FLOATS
  *   sq_out         device, one double: sum of squares, accumulated in fp64 in the same fixed order as
  *                  zb_step_report.local_sq (bit-identical for the same n and values)

@@ -16,8 +16,11 @@ __device__ __forceinline__ int nonfinite_bits(float v) {
   return (__float_as_uint(v) & 0x7F800000u) == 0x7F800000u ? 1 : 0;
 }
 
-// Level 1: one 16-byte element per thread (workgroups in index order sweep the gradient as one moving
-// front), one partial sum and one non-finite flag per workgroup.
+// Level 1: kSumsqPerThread 16-byte elements per thread, a workgroup's threads side by side in each (workgroups
+// in index order sweep the gradient as one moving front), one partial sum and one non-finite flag per
+// workgroup.
+constexpr int kSumsqPerThread = 4;
+constexpr size_t kSumsqWg4 = 256 * kSumsqPerThread;  // 16-byte elements per workgroup
 __global__ __launch_bounds__(256) void grad_sumsq_kernel(const float4* __restrict__ g, size_t n4,
                                                          double* __restrict__ partial_sq,
                                                          int* __restrict__ partial_nf) {
@@ -25,11 +28,17 @@ __global__ __launch_bounds__(256) void grad_sumsq_kernel(const float4* __restric
   __shared__ int redf[4];
   double acc = 0.0;
   int bad = 0;
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n4) {
-    const float4 v = g[i];
-    bad = nonfinite_bits(v.x) | nonfinite_bits(v.y) | nonfinite_bits(v.z) | nonfinite_bits(v.w);
-    acc = ((double)v.x * v.x + (double)v.y * v.y) + ((double)v.z * v.z + (double)v.w * v.w);
+  const size_t i0 = (size_t)blockIdx.x * kSumsqWg4 + threadIdx.x;
+  float4 v[kSumsqPerThread];
+#pragma unroll
+  for (int k = 0; k < kSumsqPerThread; ++k) {
+    const size_t i = i0 + (size_t)k * 256;
+    v[k] = i < n4 ? g[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int k = 0; k < kSumsqPerThread; ++k) {
+    bad |= nonfinite_bits(v[k].x) | nonfinite_bits(v[k].y) | nonfinite_bits(v[k].z) | nonfinite_bits(v[k].w);
+    acc += ((double)v[k].x * v[k].x + (double)v[k].y * v[k].y) + ((double)v[k].z * v[k].z + (double)v[k].w * v[k].w);
   }
   acc = wave_sum(acc);
   bad = __any(bad);
@@ -262,7 +271,7 @@ inline unsigned opt_grid(size_t n4) { return (unsigned)((n4 + 255) / 256); }
 }  // namespace
 
 size_t grad_sumsq_partials(size_t n) {
-  const size_t p1 = (n / 4 + 255) / 256, p2 = (p1 + kSumsqFan - 1) / kSumsqFan;
+  const size_t p1 = (n / 4 + kSumsqWg4 - 1) / kSumsqWg4, p2 = (p1 + kSumsqFan - 1) / kSumsqFan;
   return p1 + p2;
 }
 
@@ -271,7 +280,7 @@ static hipError_t sumsq_levels(const float* g, size_t n, double* partial_sq, int
                                int* out_nf, hipStream_t s) {
   if (n % 4 != 0 || n == 0) return hipErrorInvalidValue;
   const size_t n4 = n / 4;
-  const size_t p1 = (n4 + 255) / 256, p2 = (p1 + kSumsqFan - 1) / kSumsqFan;
+  const size_t p1 = (n4 + kSumsqWg4 - 1) / kSumsqWg4, p2 = (p1 + kSumsqFan - 1) / kSumsqFan;
   if (p1 > ((size_t)1 << 31) - 1) return hipErrorInvalidValue;
   grad_sumsq_kernel<<<(unsigned)p1, 256, 0, s>>>((const float4*)g, n4, partial_sq, partial_nf);
   hipError_t e = hipGetLastError();
@@ -353,10 +362,10 @@ hipError_t launch_adamw_rollback(float* theta, float* m, float* v, const float* 
 namespace {
 
 constexpr size_t kStaticMaxFloats = (size_t)1 << 30;  // == ZB_GRAD_NORM_STATIC_MAX_FLOATS
-constexpr size_t kStaticP1 = (kStaticMaxFloats / 4 + 255) / 256;
+constexpr size_t kStaticP1 = (kStaticMaxFloats / 4 + zb::kSumsqWg4 - 1) / zb::kSumsqWg4;
 constexpr size_t kStaticPartials = kStaticP1 + (kStaticP1 + zb::kSumsqFan - 1) / zb::kSumsqFan;
 constexpr size_t kStaticSqBytes = (kStaticPartials * sizeof(double) + 255) / 256 * 256;
-constexpr size_t kStaticBytes = kStaticSqBytes + kStaticPartials * sizeof(int);  // about 12.6 MB
+constexpr size_t kStaticBytes = kStaticSqBytes + kStaticPartials * sizeof(int);  // about 3.2 MB
 static_assert(kStaticMaxFloats == ZB_GRAD_NORM_STATIC_MAX_FLOATS, "header and kernel file disagree");
 
 static __device__ __align__(256) unsigned char scratch[kStaticBytes];

@@ -232,7 +232,7 @@ struct OptHyper {
 };
 
 // Sum of squares and non-finite flag of n gradients (n % 4 == 0) in three levels, every sum in a fixed
-// order: per workgroup of 1024 elements, per kSumsqFan of those, then one workgroup.  partial_sq and
+// order: per workgroup of 4096 elements, per kSumsqFan of those, then one workgroup.  partial_sq and
 // partial_nf need grad_sumsq_partials(n) entries each.
 constexpr int kSumsqFan = 1024;
 size_t grad_sumsq_partials(size_t n);
