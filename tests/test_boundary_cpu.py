@@ -119,3 +119,15 @@ def test_order_group_w_and_the_w_run_timing_model_match_the_oracle():
     assert zb.lib.zb_order_group_w(None, 3, 2, buf) == zb.EINVAL
     t = zb.binding.zb_pass_times(1.0, 1.0, 1.0, 0.0)
     assert zb.lib.zb_simulate_pipeline_w_runs(1, 1, buf, ctypes.byref(t), -1.0, None, None) == zb.EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is all this build covers: bench.py --gpus 2 must say so and exit without touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
